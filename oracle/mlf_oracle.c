@@ -1,0 +1,270 @@
+/*
+ * CPU oracle for the server-side hot path of MLfabric (arXiv 1907.00434).
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain definition the GPU
+ * library is checked against.  Nothing in the product path may call it, and it
+ * shares no source, header, table or helper with the GPU library.
+ *
+ * Precision: everything floating-point is IEEE binary32, round-to-nearest-even,
+ * one rounding per written operation (build with -ffp-contract=off, no
+ * fast-math, no flush-to-zero).  The paper states no precision; the required
+ * parity bar is bit-exactness in binary32, so the oracle works in binary32 and
+ * is itself pinned against exact rational / binary64 evaluations in the tests.
+ *
+ * Every loop below works on a half-open element range handed in as
+ * (pointer, n); a caller may split [0,n) into slices and call once per slice,
+ * because no element's result depends on any other element.
+ *
+ * What is computed, and where the paper defines it:
+ *
+ *  - orc_aggregate_*       Sec. 4 "Architecture": an aggregator computes the
+ *                          (weighted) sum of the updates routed to it; Sec. 3.2
+ *                          four-worker example r = g3 + g4; Sec. 5.2: the order
+ *                          chosen by the scheduler is preserved through the
+ *                          aggregator.  The sum is taken left to right in the
+ *                          scheduler's order.
+ *  - orc_apply_ordered_*   Eq. 2 (server model update with momentum),
+ *                          w_{t+1} = w_t + u_t + gamma (w_t - w_{t-1}), applied
+ *                          once per update in the given order, with u = -eta g
+ *                          (Eq. 1 without its regulariser) and the history
+ *                          h = w_t - w_{t-1} (Sec. 3.3, definition of h^0) kept
+ *                          in the momentum buffer:  h <- gamma h - eta g ;
+ *                          w <- w + h.
+ *  - orc_aggregate_apply_* Sec. 5.4 "Synchronous SGD/PS": the updates of one
+ *                          iteration are aggregated and the aggregate is applied
+ *                          to the model once (one step of Eq. 2 with g = sum).
+ *  - orc_scatter_add       Sec. 6 "Datasets and ML models": an LDA worker's
+ *                          update is a numerical update to the word-topic count
+ *                          matrix; here it arrives as (word, topic, delta)
+ *                          triples that are added into the matrix and into the
+ *                          per-topic totals.
+ */
+#include <stddef.h>
+#include <stdint.h>
+#include <string.h>
+
+/* bfloat16 -> binary32: the 16 stored bits are the top half of the float. */
+static float widen_bf16(uint16_t x)
+{
+    uint32_t bits = (uint32_t)x << 16;
+    float f;
+    memcpy(&f, &bits, sizeof f);
+    return f;
+}
+
+float orc_widen_bf16(uint16_t x) { return widen_bf16(x); }
+
+/* ------------------------------------------------------------------------ */
+/* Weighted, ordered sum of M of the K update vectors (Sec. 4; Sec. 5.2).     */
+/*   out[i] = sum_{t=0}^{M-1} weights[order[t]] * U[order[t]][i]              */
+/* summed left to right.  The accumulator starts as the first term (no        */
+/* leading "0 +"), so M = 1 with no weights is a bit copy and -0 survives.    */
+/* weights == NULL means every weight is 1 and no multiply is performed.      */
+/* M == 0 gives +0.                                                           */
+/* ------------------------------------------------------------------------ */
+static float ordered_sum_f32(const float *const *U, int64_t i,
+                             const int32_t *order, int M, const float *weights)
+{
+    float acc = 0.0f;
+    for (int t = 0; t < M; ++t) {
+        int j = order[t];
+        float term = U[j][i];
+        if (weights) {
+            term = weights[j] * term;
+        }
+        if (t == 0) {
+            acc = term;
+        } else {
+            acc = acc + term;
+        }
+    }
+    return acc;
+}
+
+static float ordered_sum_bf16(const uint16_t *const *U, int64_t i,
+                              const int32_t *order, int M, const float *weights)
+{
+    float acc = 0.0f;
+    for (int t = 0; t < M; ++t) {
+        int j = order[t];
+        float term = widen_bf16(U[j][i]);
+        if (weights) {
+            term = weights[j] * term;
+        }
+        if (t == 0) {
+            acc = term;
+        } else {
+            acc = acc + term;
+        }
+    }
+    return acc;
+}
+
+void orc_aggregate_f32(const float *const *U, int K, int64_t n,
+                       const int32_t *order, int M, const float *weights,
+                       float *out)
+{
+    (void)K;
+    for (int64_t i = 0; i < n; ++i) {
+        out[i] = ordered_sum_f32(U, i, order, M, weights);
+    }
+}
+
+void orc_aggregate_bf16(const uint16_t *const *U, int K, int64_t n,
+                        const int32_t *order, int M, const float *weights,
+                        float *out)
+{
+    (void)K;
+    for (int64_t i = 0; i < n; ++i) {
+        out[i] = ordered_sum_bf16(U, i, order, M, weights);
+    }
+}
+
+/* ------------------------------------------------------------------------ */
+/* One application of Eq. 2 with u = -lr * g.                                 */
+/* With a history buffer:   h <- mu*h - lr*g ;  w <- w + h                    */
+/* (two products, one difference, one sum: four roundings).                   */
+/* Without one (plain SGD):  w <- w - lr*g.                                    */
+/* ------------------------------------------------------------------------ */
+static void server_step(float *w, float *h, int have_h, float g, float lr,
+                        float mu)
+{
+    float q = lr * g;
+    if (have_h) {
+        float p = mu * (*h);
+        float hn = p - q;
+        *h = hn;
+        *w = *w + hn;
+    } else {
+        *w = *w - q;
+    }
+}
+
+/* Eq. 2 folded over the scheduler's sequence, one update after another. */
+void orc_apply_ordered_f32(float *model, float *momentum,
+                           const float *const *U, int K, int64_t n,
+                           const int32_t *order, int M, float lr, float mu)
+{
+    (void)K;
+    for (int64_t i = 0; i < n; ++i) {
+        float w = model[i];
+        float h = momentum ? momentum[i] : 0.0f;
+        for (int t = 0; t < M; ++t) {
+            server_step(&w, &h, momentum != NULL, U[order[t]][i], lr, mu);
+        }
+        model[i] = w;
+        if (momentum) {
+            momentum[i] = h;
+        }
+    }
+}
+
+void orc_apply_ordered_bf16(float *model, float *momentum,
+                            const uint16_t *const *U, int K, int64_t n,
+                            const int32_t *order, int M, float lr, float mu)
+{
+    (void)K;
+    for (int64_t i = 0; i < n; ++i) {
+        float w = model[i];
+        float h = momentum ? momentum[i] : 0.0f;
+        for (int t = 0; t < M; ++t) {
+            server_step(&w, &h, momentum != NULL,
+                        widen_bf16(U[order[t]][i]), lr, mu);
+        }
+        model[i] = w;
+        if (momentum) {
+            momentum[i] = h;
+        }
+    }
+}
+
+/* ------------------------------------------------------------------------ */
+/* Synchronous iteration (Sec. 5.4): aggregate, then ONE step of Eq. 2 with   */
+/* g = the aggregate.  out (optional) receives the aggregate.                 */
+/* ------------------------------------------------------------------------ */
+void orc_aggregate_apply_f32(float *model, float *momentum, float *out,
+                             const float *const *U, int K, int64_t n,
+                             const int32_t *order, int M, const float *weights,
+                             float lr, float mu)
+{
+    (void)K;
+    for (int64_t i = 0; i < n; ++i) {
+        float a = ordered_sum_f32(U, i, order, M, weights);
+        if (out) {
+            out[i] = a;
+        }
+        float w = model[i];
+        float h = momentum ? momentum[i] : 0.0f;
+        server_step(&w, &h, momentum != NULL, a, lr, mu);
+        model[i] = w;
+        if (momentum) {
+            momentum[i] = h;
+        }
+    }
+}
+
+void orc_aggregate_apply_bf16(float *model, float *momentum, float *out,
+                              const uint16_t *const *U, int K, int64_t n,
+                              const int32_t *order, int M, const float *weights,
+                              float lr, float mu)
+{
+    (void)K;
+    for (int64_t i = 0; i < n; ++i) {
+        float a = ordered_sum_bf16(U, i, order, M, weights);
+        if (out) {
+            out[i] = a;
+        }
+        float w = model[i];
+        float h = momentum ? momentum[i] : 0.0f;
+        server_step(&w, &h, momentum != NULL, a, lr, mu);
+        model[i] = w;
+        if (momentum) {
+            momentum[i] = h;
+        }
+    }
+}
+
+/* ------------------------------------------------------------------------ */
+/* LDA count deltas (Sec. 6): for every (word, topic, delta) triple            */
+/*   counts[word*T + topic] += delta ;  totals[topic] += delta                */
+/* Additions wrap modulo 2^32 (done on unsigned values so that C defines it). */
+/* A triple whose word or topic is out of range is skipped and counted.       */
+/*                                                                            */
+/* The caller may restrict which part of the state this call owns: counts     */
+/* rows in [word_lo, word_hi) and totals entries in [topic_lo, topic_hi) are   */
+/* updated, the rest is left alone; rejected triples are counted only when    */
+/* count_rejected is non-zero.  The full operation is one call with           */
+/* (0, V, 0, T, 1); slices that partition both ranges give the same state.    */
+/* Returns the number of rejected triples it counted.                         */
+/* ------------------------------------------------------------------------ */
+int64_t orc_scatter_add(int32_t *counts, int32_t *totals, int32_t V, int32_t T,
+                        const int32_t *const *triples, const int64_t *n_triples,
+                        int K, int32_t word_lo, int32_t word_hi,
+                        int32_t topic_lo, int32_t topic_hi, int count_rejected)
+{
+    int64_t rejected = 0;
+    for (int k = 0; k < K; ++k) {
+        const int32_t *tr = triples[k];
+        for (int64_t r = 0; r < n_triples[k]; ++r) {
+            int32_t word = tr[3 * r + 0];
+            int32_t topic = tr[3 * r + 1];
+            int32_t delta = tr[3 * r + 2];
+            if (word < 0 || word >= V || topic < 0 || topic >= T) {
+                if (count_rejected) {
+                    ++rejected;
+                }
+                continue;
+            }
+            if (word >= word_lo && word < word_hi) {
+                int64_t cell = (int64_t)word * T + topic;
+                counts[cell] =
+                    (int32_t)((uint32_t)counts[cell] + (uint32_t)delta);
+            }
+            if (totals && topic >= topic_lo && topic < topic_hi) {
+                totals[topic] =
+                    (int32_t)((uint32_t)totals[topic] + (uint32_t)delta);
+            }
+        }
+    }
+    return rejected;
+}

@@ -1,0 +1,125 @@
+"""Pins for the oracle's LDA count-delta scatter-add (Sec. 6 of the paper: a
+worker's update is a numerical update to the word-topic matrix).  CPU only."""
+import numpy as np
+import pytest
+
+import oracle
+import workloads as W
+
+
+def small_cfg(**kw):
+    base = dict(V=301, T=17, K=3, m=5000)
+    base.update(kw)
+    return W.scaled(W.CONFIGS["cfg5"], **base)
+
+
+def host_inputs(cfg, **kw):
+    d = W.sparse_inputs(cfg, "cpu", **kw)
+    return (W.to_host(d["counts"]), W.to_host(d["totals"]),
+            [W.to_host(t) for t in d["triples"]])
+
+
+def test_hand_case(golden):
+    g = {k: np.array([int(x) for x in v], dtype=np.int32)
+         for k, v in golden("scatter_tiny.txt").items()}
+    V, T = int(g["V"][0]), int(g["T"][0])
+    counts, totals = g["counts0"].copy(), g["totals0"].copy()
+    tr = [g["triples0"].reshape(-1, 3).copy(), g["triples1"].reshape(-1, 3).copy()]
+    rej = oracle.scatter_add(counts, totals, V, T, tr)
+    assert np.array_equal(counts, g["counts"])
+    assert np.array_equal(totals, g["totals"])
+    assert rej == int(g["rejected"][0])
+
+
+@pytest.mark.parametrize("init", ["zeros", "random"])
+def test_equals_numpy_add_at_and_bincount(init):
+    cfg = small_cfg()
+    counts, totals, tr = host_inputs(cfg, init=init)
+    c0, t0 = counts.copy(), totals.copy()
+    rej = oracle.scatter_add(counts, totals, cfg.V, cfg.T, tr)
+    allt = np.concatenate(tr).astype(np.int64)
+    flat = allt[:, 0] * cfg.T + allt[:, 1]
+    ref = c0.astype(np.int64)
+    np.add.at(ref, flat, allt[:, 2])
+    assert rej == 0 and np.array_equal(counts, ref)
+    hist = np.bincount(flat, weights=allt[:, 2], minlength=cfg.V * cfg.T)
+    assert np.array_equal(counts - c0, hist.astype(np.int64))
+    tref = t0 + np.bincount(allt[:, 1], weights=allt[:, 2], minlength=cfg.T).astype(np.int64)
+    assert np.array_equal(totals, tref)
+
+
+def test_mass_is_conserved_and_totals_are_column_sums():
+    cfg = small_cfg()
+    counts, totals, tr = host_inputs(cfg, init="random", n_invalid=9)
+    c0, t0 = counts.copy(), totals.copy()
+    rej = oracle.scatter_add(counts, totals, cfg.V, cfg.T, tr)
+    assert rej == 9 * cfg.K
+    allt = np.concatenate(tr).astype(np.int64)
+    ok = (allt[:, 0] >= 0) & (allt[:, 0] < cfg.V) & (allt[:, 1] >= 0) & (allt[:, 1] < cfg.T)
+    assert counts.astype(np.int64).sum() - c0.astype(np.int64).sum() == allt[ok, 2].sum()
+    assert np.array_equal(totals - t0, (counts - c0).reshape(cfg.V, cfg.T).sum(axis=0))
+    assert np.array_equal(totals, counts.reshape(cfg.V, cfg.T).sum(axis=0))
+
+
+def test_negated_deltas_restore_the_state():
+    cfg = small_cfg()
+    counts, totals, tr = host_inputs(cfg, init="random")
+    c0, t0 = counts.copy(), totals.copy()
+    oracle.scatter_add(counts, totals, cfg.V, cfg.T, tr)
+    assert not np.array_equal(counts, c0)
+    neg = [t * np.array([1, 1, -1], dtype=np.int32) for t in tr]
+    oracle.scatter_add(counts, totals, cfg.V, cfg.T, neg)
+    assert np.array_equal(counts, c0) and np.array_equal(totals, t0)
+
+
+def test_result_does_not_depend_on_order_or_split():
+    cfg = small_cfg()
+    counts, totals, tr = host_inputs(cfg)
+    oracle.scatter_add(counts, totals, cfg.V, cfg.T, tr)
+    allt = np.concatenate(tr)
+    rng = np.random.default_rng(1)
+    shuffled = allt[rng.permutation(len(allt))]
+    parts = [np.ascontiguousarray(p) for p in np.array_split(shuffled, [10, 4000, 4001])]
+    c2 = np.zeros_like(counts)
+    t2 = np.zeros_like(totals)
+    oracle.scatter_add(c2, t2, cfg.V, cfg.T, parts)
+    assert np.array_equal(counts, c2) and np.array_equal(totals, t2)
+
+
+def test_additions_wrap_modulo_2_32():
+    counts = np.array([2 ** 31 - 1, -2 ** 31], dtype=np.int32)
+    totals = np.array([2 ** 31 - 1], dtype=np.int32)
+    tr = [np.array([[0, 0, 1], [1, 0, -1]], dtype=np.int32)]
+    oracle.scatter_add(counts, totals, 2, 1, tr)
+    assert counts.tolist() == [-2 ** 31, 2 ** 31 - 1]
+    assert totals.tolist() == [2 ** 31 - 1]
+
+
+def test_totals_are_optional_and_empty_input_is_fine():
+    counts = np.zeros(6, dtype=np.int32)
+    tr = [np.array([[1, 1, 5]], dtype=np.int32), np.zeros((0, 3), dtype=np.int32)]
+    assert oracle.scatter_add(counts, None, 3, 2, tr) == 0
+    assert counts.tolist() == [0, 0, 0, 5, 0, 0]
+    assert oracle.scatter_add(counts, None, 3, 2, []) == 0
+
+
+def test_thread_partition_gives_the_same_state():
+    cfg = small_cfg(m=20000)
+    counts, totals, tr = host_inputs(cfg, init="random", n_invalid=3)
+    c1, t1 = counts.copy(), totals.copy()
+    r1 = oracle.scatter_add(c1, t1, cfg.V, cfg.T, tr, threads=1)
+    c2, t2 = counts.copy(), totals.copy()
+    r2 = oracle.scatter_add(c2, t2, cfg.V, cfg.T, tr, threads=6)
+    assert r1 == r2 and np.array_equal(c1, c2) and np.array_equal(t1, t2)
+
+
+def test_generator_follows_the_truncated_zipf_law():
+    cfg = small_cfg(V=1000, T=10, K=1, m=400000)
+    tr = W.to_host(W.sparse_triples(cfg, 0, "cpu"))
+    assert tr[:, 0].min() >= 0 and tr[:, 0].max() < cfg.V
+    assert set(np.unique(tr[:, 2]).tolist()) == {-1, 1}
+    freq = np.bincount(tr[:, 0], minlength=cfg.V) / cfg.m
+    pmf = np.arange(1, cfg.V + 1) ** -1.1
+    pmf /= pmf.sum()
+    assert abs(freq[0] - pmf[0]) < 0.01 and abs(freq[:10].sum() - pmf[:10].sum()) < 0.01
+    assert abs(tr[:, 2].mean()) < 0.01
