@@ -1,0 +1,259 @@
+#!/usr/bin/env python3
+"""Benchmark of the MI355X hot path: effective HBM GB/s of the K-way
+aggregate + apply (and of the other calls) on seeded synthetic updates.
+
+One "step" is one call of the workload's entry point over one batch of K
+updates that are already resident in HBM.  The default workload is the
+ResNet-50-sized configuration (K = 16 binary32 updates of 25,557,032 elements,
+SGD with momentum); `--workload cfg1..cfg5` selects another one.  "Effective"
+bandwidth is ALGORITHMIC bytes (each update once, model and momentum read and
+written once) divided by time, so redundant traffic lowers it.
+
+Prints one JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--no-rows", action="store_true",
+                    help="skip the extra per-call measurements of the other configurations")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 1 GiB device copy a few times (reference for "
+                         "hardware byte counters)")
+    return ap.parse_args()
+
+
+class DenseJob:
+    """Device-resident inputs of one dense configuration and its entry point."""
+
+    def __init__(self, cfg, mlf, W, torch, call=None):
+        self.cfg, self.mlf = cfg, mlf
+        self.call = call or cfg.call
+        self.d = W.dense_inputs(cfg, "cuda:0")
+        d = self.d
+        self.out = None
+        if self.call == "aggregate":
+            self.out = torch.empty(cfg.n, device="cuda:0")
+        state = {"aggregate": 4, "apply_ordered": 16 if d["momentum"] is not None else 8,
+                 "aggregate_apply": 16 if d["momentum"] is not None else 8}[self.call]
+        self.bytes = (cfg.in_bytes * len(d["order"]) + state) * cfg.n
+        self.units = len(d["order"]) * cfg.n          # update elements consumed per step
+        self.kernel = "dense_kernel"
+
+    def step(self):
+        d, m = self.d, self.mlf
+        if self.call == "aggregate":
+            m.mlf_aggregate(d["updates"], d["order"], d["weights"], self.out)
+        elif self.call == "apply_ordered":
+            m.mlf_apply_ordered(d["model"], d["momentum"], d["updates"], d["order"], d["lr"], d["mu"])
+        else:
+            m.mlf_aggregate_apply(d["model"], d["momentum"], None, d["updates"], d["order"],
+                                  d["weights"], d["lr"], d["mu"])
+
+
+class SparseJob:
+    def __init__(self, cfg, mlf, W, torch):
+        self.cfg, self.mlf = cfg, mlf
+        self.call = "sparse_scatter_add"
+        self.d = W.sparse_inputs(cfg, "cuda:0")
+        total = cfg.K * cfg.m
+        nbytes = mlf.mlf_sparse_workspace_bytes(cfg.V, cfg.T, total)
+        self.ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device="cuda:0")
+        self.bytes = cfg.algorithmic_bytes()
+        self.units = total                             # triples per step
+        self.kernel = "scatter"
+
+    def step(self):
+        d = self.d
+        self.mlf.mlf_sparse_scatter_add(d["counts"], d["totals"], self.cfg.V, self.cfg.T,
+                                        d["triples"], workspace=self.ws)
+
+
+def time_steps(torch, job, steps, warmup):
+    """Wall time and HIP-event time (on the launch stream) of `steps` steps."""
+    for _ in range(warmup):
+        job.step()
+    torch.cuda.synchronize()
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    start.record()
+    for _ in range(steps):
+        job.step()
+    stop.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / steps
+    event_ms = start.elapsed_time(stop) / steps
+    return wall_ms, event_ms
+
+
+def cpu_baseline(job, W, torch):
+    """The oracle, as it stands, on a bounded sample of the same workload."""
+    import numpy as np
+
+    import oracle
+    threads = min(16, len(os.sched_getaffinity(0)))
+    cfg, d = job.cfg, job.d
+    if job.call == "sparse_scatter_add":
+        tr = [W.to_host(t[: 500_000]) for t in d["triples"][:8]]
+        counts = np.zeros(cfg.V * cfg.T, dtype=np.int32)
+        totals = np.zeros(cfg.T, dtype=np.int32)
+        n_units = sum(t.shape[0] for t in tr)
+        nbytes = 20 * n_units
+        sample = f"first 500,000 triples of 8 of the {cfg.K} buffers into the full {cfg.V}x{cfg.T} matrix"
+
+        def run(th):
+            oracle.scatter_add(counts, totals, cfg.V, cfg.T, tr, threads=th)
+    else:
+        n_s = min(cfg.n, 4_000_000)
+        ups = [W.to_host(u[:n_s]) for u in d["updates"]]
+        w = W.to_host(d["model"][:n_s])
+        h = W.to_host(d["momentum"][:n_s]) if d["momentum"] is not None else None
+        n_units = len(d["order"]) * n_s
+        nbytes = job.bytes // cfg.n * n_s
+        sample = f"first {n_s:,} of {cfg.n:,} elements of all {cfg.K} updates"
+
+        def run(th):
+            if job.call == "apply_ordered":
+                oracle.apply_ordered(w, h, ups, d["order"], d["lr"], d["mu"], threads=th)
+            elif job.call == "aggregate":
+                oracle.aggregate(ups, d["order"], d["weights"], threads=th)
+            else:
+                oracle.aggregate_apply(w, h, ups, d["order"], d["weights"], d["lr"], d["mu"],
+                                       threads=th)
+
+    def timed(th, budget_s):
+        run(th)                                        # touch pages once
+        reps, t0 = 0, time.perf_counter()
+        while True:
+            run(th)
+            reps += 1
+            el = time.perf_counter() - t0
+            if el >= budget_s and reps >= 2:
+                return el / reps
+
+    t_multi = timed(threads, 6.0)
+    t_single = timed(1, 4.0)
+    return {
+        "value": round(nbytes / t_multi / 1e9, 3), "unit": "GB/s", "cores": threads,
+        "kind": "oracle", "sample": sample,
+        "elements_per_s": round(n_units / t_multi, 1),
+        "single_thread_value": round(nbytes / t_single / 1e9, 3),
+    }
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no sharding, no collectives); "
+              "--gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import paper_1907_00434_amd as mlf
+    import workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    torch.cuda.set_device(0)
+
+    def make(name, call=None):
+        cfg = W.CONFIGS[name]
+        if isinstance(cfg, W.SparseConfig):
+            return SparseJob(cfg, mlf, W, torch)
+        return DenseJob(cfg, mlf, W, torch, call)
+
+    job = make(args.workload)
+    wall_ms, event_ms = time_steps(torch, job, args.steps, args.warmup)
+    gbs = job.bytes / (wall_ms * 1e-3) / 1e9
+    achieved = job.bytes / (event_ms * 1e-3) / 1e9
+    cfg = job.cfg
+    line = {
+        "metric": "effective HBM GB/s (and % of peak) for K-way aggregate+apply; elements/s",
+        "value": round(gbs, 2),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(wall_ms, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32" if args.workload == "cfg5" or cfg.dtype == "f32" else "f32 (bf16 inputs)",
+        "data": "synthetic",
+        "percent_of_peak": round(100.0 * gbs / HBM_PEAK_GBS, 2),
+        "elements_per_s": round(job.units / (wall_ms * 1e-3), 1),
+        "config": {
+            "workload": f"{args.workload}: {job.call}",
+            "K": cfg.K,
+            **({"V": cfg.V, "T": cfg.T, "triples": cfg.K * cfg.m} if args.workload == "cfg5"
+               else {"n": cfg.n, "update_dtype": cfg.dtype, "momentum": cfg.momentum,
+                     "lr": cfg.lr, "mu": cfg.mu}),
+            "algorithmic_bytes_per_step": job.bytes,
+        },
+        "roofline": {
+            "bound": "hbm",
+            "achieved": round(achieved, 2),
+            "peak": HBM_PEAK_GBS,
+            "unit": "GB/s",
+            "frac": round(achieved / HBM_PEAK_GBS, 4),
+            "traffic": None,
+            "kernel": job.kernel,
+            "avg_launch_ms": round(event_ms, 5),
+        },
+    }
+    if args.workload == "cfg5":
+        line["dtype"] = "int32"
+
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(job, W, torch)
+
+    if args.copy_calibration:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda:0").normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
+    if not args.no_rows:
+        del job
+        torch.cuda.empty_cache()
+        rows = {}
+        plan = [("cfg1", None), ("cfg2", "aggregate"), ("cfg2", None), ("cfg3", None),
+                ("cfg4", None), ("cfg5", None)]
+        for name, call in plan:
+            j = make(name, call)
+            _, ev = time_steps(torch, j, 20, 3)
+            key = f"{name}:{j.call}"
+            rows[key] = {"ms": round(ev, 5), "GB/s": round(j.bytes / ev / 1e6, 1),
+                         "frac_of_peak": round(j.bytes / ev / 1e6 / HBM_PEAK_GBS, 4),
+                         "units_per_s": round(j.units / (ev * 1e-3), 1)}
+            del j
+            torch.cuda.empty_cache()
+        line["rows"] = rows
+
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

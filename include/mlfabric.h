@@ -1,0 +1,170 @@
+/*
+ * mlfabric.h -- C ABI of the MI355X (gfx950) library for the server-side hot
+ * path of MLfabric (arXiv 1907.00434): the K-way reduction of worker update
+ * vectors in the scheduler's order, the application of the aggregate or of the
+ * ordered update sequence to the model, and the scatter-add of LDA count deltas.
+ *
+ * Common conventions
+ * ------------------
+ *  - "host" arguments (pointer tables, order, weights, triple counts) describe
+ *    the scheduler's decisions.  They are read before the call returns and may
+ *    be freed or changed right after it.
+ *  - "device" arguments are HIP device pointers owned by the caller.  The
+ *    library allocates no memory, keeps no state between calls and frees
+ *    nothing.  Device buffers must stay valid until the stream has run the
+ *    enqueued work.
+ *  - Every call only enqueues kernels on `stream` (a hipStream_t; NULL is the
+ *    default stream) and returns; it never synchronises the device.
+ *  - Errors are reported through the return code only; nothing is enqueued when
+ *    a call returns an error other than MLF_EHIP.
+ *  - Dense vectors: n contiguous elements.  Updates are MLF_F32 (IEEE binary32)
+ *    or MLF_BF16 (bfloat16, widened exactly to binary32 before any arithmetic).
+ *    model, momentum and out are always binary32.  Pointers must be aligned to
+ *    their element size (else MLF_EALIGN); when every pointer of a call is
+ *    16-byte aligned the 128-bit path is taken, otherwise a slower
+ *    element-wise path gives the same bits.
+ *  - Arithmetic is binary32, round-to-nearest-even, one rounding per operation
+ *    written below (no fused multiply-add), subnormals kept.  For a fixed
+ *    `order` the result is reproducible bit for bit.
+ *  - `order` lists n_order <= K distinct worker indices in [0, K): the sequence
+ *    in which the scheduler committed the updates (Sec. 5.1-5.2 of the paper).
+ *    Workers that are not listed were dropped by the scheduler (Sec. 5.1,
+ *    deadline / look-ahead drops) and are ignored; their pointers may be NULL.
+ *  - model / momentum / out must not overlap each other or any listed update
+ *    (MLF_EINVAL).
+ */
+#ifndef MLFABRIC_H
+#define MLFABRIC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    MLF_OK = 0,
+    MLF_EINVAL = -1,        /* bad argument (see each call)                    */
+    MLF_EALIGN = -2,        /* a device pointer is not aligned to its element  */
+    MLF_EUNSUPPORTED = -3,  /* K > MLF_MAX_K                                   */
+    MLF_EHIP = -4           /* the HIP runtime refused the launch              */
+} mlf_status;
+
+typedef enum { MLF_F32 = 0, MLF_BF16 = 1 } mlf_dtype;
+
+typedef void *mlf_stream;   /* a hipStream_t */
+
+#define MLF_MAX_K 64        /* most updates (or triple buffers) per call */
+
+/*
+ * Aggregator (Sec. 4 "Architecture": aggregators compute the (weighted) sum of
+ * incoming updates; Sec. 3.2 example r = g3 + g4; Sec. 5.2: the scheduler's
+ * order is kept through the aggregator).
+ *
+ *   out[i] = sum_{t=0}^{n_order-1} weights[order[t]] * U_{order[t]}[i]
+ *
+ * summed left to right in that order; each product is rounded, then each sum.
+ * The first term starts the accumulator (no "0 +").  weights == NULL means all
+ * weights are 1 and no multiply is done.  n_order == 0 writes +0 everywhere;
+ * n == 0 does nothing.
+ *
+ *   update_ptrs  host   K device pointers, one vector of n elements per worker
+ *   order        host   n_order indices (may be NULL when n_order == 0)
+ *   weights      host   K floats indexed by worker, or NULL
+ *   out          device binary32[n]
+ *
+ * MLF_EINVAL: K < 1, n < 0, n_order outside [0, K], an index outside [0, K) or
+ * listed twice, NULL out / update_ptrs / a listed update, overlap.
+ */
+mlf_status mlf_aggregate(const void *const *update_ptrs, int K, int64_t n,
+                         mlf_dtype dtype, const int32_t *order, int n_order,
+                         const float *weights, float *out, mlf_stream stream);
+
+/*
+ * Server update callback (Eq. 2 of the paper, SGD with momentum)
+ *   w_{t+1} = w_t + u_t + gamma (w_t - w_{t-1}),   u = -lr * g  (Eq. 1),
+ * applied once per listed update, in order, in ONE pass over the model.  The
+ * momentum buffer holds the history h = w_t - w_{t-1} (Sec. 3.3, h^0).  For
+ * each element and each t = 0 .. n_order-1:
+ *
+ *   p = mu * h ;  q = lr * g_{order[t]} ;  h = p - q ;  w = w + h
+ *
+ * momentum == NULL selects plain SGD (mu is ignored):  q = lr * g ; w = w - q.
+ * Note that h is the paper's history, not the velocity of the v <- mu v + g
+ * formulation; for constant lr the two give the same trajectory with
+ * h = -lr v but round differently.
+ *
+ *   model     device binary32[n], read and written
+ *   momentum  device binary32[n], read and written, or NULL
+ *   others    as for mlf_aggregate
+ *
+ * n_order == 0 or n == 0 does nothing.  MLF_EINVAL as for mlf_aggregate
+ * (model in place of out).
+ */
+mlf_status mlf_apply_ordered(float *model, float *momentum,
+                             const void *const *update_ptrs, int K, int64_t n,
+                             mlf_dtype dtype, const int32_t *order, int n_order,
+                             float lr, float mu, mlf_stream stream);
+
+/*
+ * Synchronous iteration (Sec. 5.4 "Synchronous SGD/PS": the updates of an
+ * iteration are aggregated and applied to the model): the sum of
+ * mlf_aggregate, kept in registers, followed by ONE step of mlf_apply_ordered
+ * with g = that sum.  Bit-identical to calling mlf_aggregate and then
+ * mlf_apply_ordered on its output.  out_or_null (device binary32[n]) also
+ * receives the aggregate when given.  n_order == 0 takes the step with g = +0
+ * (the momentum term still moves the model).
+ */
+mlf_status mlf_aggregate_apply(float *model, float *momentum, float *out_or_null,
+                               const void *const *update_ptrs, int K, int64_t n,
+                               mlf_dtype dtype, const int32_t *order, int n_order,
+                               const float *weights, float lr, float mu,
+                               mlf_stream stream);
+
+/*
+ * LDA count deltas (Sec. 6 "Datasets and ML models": each LDA worker computes a
+ * numerical update to the word-topic matrix).  For every triple
+ * (word, topic, delta) of every buffer:
+ *
+ *   counts[word * T + topic] += delta ;  totals[topic] += delta
+ *
+ * in int32 arithmetic that wraps modulo 2^32.  Integer addition commutes, so
+ * the result does not depend on execution order.  A triple with word outside
+ * [0, V) or topic outside [0, T) is skipped and counted in *n_rejected.
+ *
+ *   counts        device int32[V*T], row-major by word; read and written
+ *   totals        device int32[T] or NULL
+ *   triple_ptrs   host   K device pointers; buffer k holds n_triples[k] triples
+ *                        as 3 consecutive int32 (word, topic, delta), 4-byte
+ *                        aligned
+ *   n_triples     host   K counts (>= 0)
+ *   workspace     device scratch of at least
+ *                        mlf_sparse_workspace_bytes(V, T, total) bytes, 256-byte
+ *                        aligned, contents undefined before and after; with NULL
+ *                        (or fewer bytes) the call takes the direct path, which
+ *                        needs none and gives the same result
+ *   n_rejected    device int32 counter that the call ADDS to (the caller clears
+ *                        it), or NULL
+ *
+ * MLF_EINVAL: V < 1, T < 1, V*T >= 2^31 * 2^31 (overflow), K < 0, a negative
+ * count, a NULL buffer with a positive count, NULL counts.  K == 0 or no
+ * triples does nothing.  MLF_EUNSUPPORTED: K > MLF_MAX_K.
+ */
+mlf_status mlf_sparse_scatter_add(int32_t *counts, int32_t *totals, int32_t V,
+                                  int32_t T, const int32_t *const *triple_ptrs,
+                                  const int64_t *n_triples, int K,
+                                  void *workspace, size_t workspace_bytes,
+                                  int32_t *n_rejected, mlf_stream stream);
+
+/* Scratch the binned path of mlf_sparse_scatter_add needs for this problem
+ * size (0 when that path would not be used). */
+size_t mlf_sparse_workspace_bytes(int32_t V, int32_t T, int64_t total_triples);
+
+/* Static, human-readable name of a status code. */
+const char *mlf_status_string(mlf_status status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MLFABRIC_H */

@@ -1,0 +1,194 @@
+"""ctypes binding of libmlfabric_hip.so: same names as the C ABI, argument
+marshalling only.  torch is used for device memory and the current stream.
+
+There is no fallback: if the HIP library cannot be loaded the calls raise.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+import torch
+
+from . import build as _build
+
+MLF_MAX_K = 64
+MLF_OK, MLF_EINVAL, MLF_EALIGN, MLF_EUNSUPPORTED, MLF_EHIP = 0, -1, -2, -3, -4
+MLF_F32, MLF_BF16 = 0, 1
+
+_c = ctypes
+_lib = None
+
+
+class MlfError(RuntimeError):
+    def __init__(self, status: int):
+        self.status = int(status)
+        super().__init__(mlf_status_string(status))
+
+
+def library_path() -> str:
+    return _build.LIB
+
+
+def raw():
+    """The loaded ctypes library (built first if no built copy is there)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not _build.is_built():
+        _build.build()
+    lib = _c.CDLL(_build.LIB)
+    vpp = _c.POINTER(_c.c_void_p)
+    i32p = _c.POINTER(_c.c_int32)
+    f32p = _c.POINTER(_c.c_float)
+    lib.mlf_aggregate.argtypes = [vpp, _c.c_int, _c.c_int64, _c.c_int, i32p, _c.c_int,
+                                  f32p, _c.c_void_p, _c.c_void_p]
+    lib.mlf_aggregate.restype = _c.c_int
+    lib.mlf_apply_ordered.argtypes = [_c.c_void_p, _c.c_void_p, vpp, _c.c_int, _c.c_int64,
+                                      _c.c_int, i32p, _c.c_int, _c.c_float, _c.c_float,
+                                      _c.c_void_p]
+    lib.mlf_apply_ordered.restype = _c.c_int
+    lib.mlf_aggregate_apply.argtypes = [_c.c_void_p, _c.c_void_p, _c.c_void_p, vpp, _c.c_int,
+                                        _c.c_int64, _c.c_int, i32p, _c.c_int, f32p,
+                                        _c.c_float, _c.c_float, _c.c_void_p]
+    lib.mlf_aggregate_apply.restype = _c.c_int
+    lib.mlf_sparse_scatter_add.argtypes = [_c.c_void_p, _c.c_void_p, _c.c_int32, _c.c_int32,
+                                           vpp, _c.POINTER(_c.c_int64), _c.c_int,
+                                           _c.c_void_p, _c.c_size_t, _c.c_void_p,
+                                           _c.c_void_p]
+    lib.mlf_sparse_scatter_add.restype = _c.c_int
+    lib.mlf_sparse_workspace_bytes.argtypes = [_c.c_int32, _c.c_int32, _c.c_int64]
+    lib.mlf_sparse_workspace_bytes.restype = _c.c_size_t
+    lib.mlf_status_string.argtypes = [_c.c_int]
+    lib.mlf_status_string.restype = _c.c_char_p
+    _lib = lib
+    return lib
+
+
+def mlf_status_string(status: int) -> str:
+    return raw().mlf_status_string(int(status)).decode()
+
+
+def _stream(stream):
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    return getattr(stream, "cuda_stream", stream)
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError("device tensors expected")
+    return t.data_ptr()
+
+
+def _dense_tables(updates, order, weights, n):
+    K = len(updates)
+    kind = None
+    tab = (_c.c_void_p * max(K, 1))()
+    for j, u in enumerate(updates):
+        if u is None:
+            tab[j] = None
+            continue
+        if u.dtype == torch.float32:
+            k = MLF_F32
+        elif u.dtype == torch.bfloat16:
+            k = MLF_BF16
+        else:
+            raise TypeError("updates must be float32 or bfloat16")
+        if kind is not None and k != kind:
+            raise TypeError("all updates of a call share one dtype")
+        kind = k
+        if u.dim() != 1 or not u.is_contiguous() or u.numel() < n:
+            raise ValueError("updates must be contiguous vectors of at least n elements")
+        tab[j] = _ptr(u)
+    if kind is None:
+        kind = MLF_F32
+    o = np.ascontiguousarray(np.asarray(order, dtype=np.int32).reshape(-1))
+    op = o.ctypes.data_as(_c.POINTER(_c.c_int32))
+    w = wp = None
+    if weights is not None:
+        w = np.ascontiguousarray(np.asarray(weights, dtype=np.float32).reshape(-1))
+        if w.shape[0] != K:
+            raise ValueError("weights must have one entry per worker")
+        wp = w.ctypes.data_as(_c.POINTER(_c.c_float))
+    return tab, K, kind, o, op, w, wp
+
+
+def _state(t, n, name):
+    if t is None:
+        return
+    if t.dtype != torch.float32 or t.dim() != 1 or not t.is_contiguous() or t.numel() < n:
+        raise ValueError(f"{name} must be a contiguous float32 vector of at least n elements")
+
+
+def _done(status, check):
+    if check and status != MLF_OK:
+        raise MlfError(status)
+    return status
+
+
+def mlf_aggregate(updates, order, weights, out, n=None, stream=None, check=True):
+    """out[i] = sum_t weights[order[t]] * updates[order[t]][i], left to right."""
+    n = out.numel() if n is None else int(n)
+    _state(out, n, "out")
+    tab, K, kind, o, op, w, wp = _dense_tables(updates, order, weights, n)
+    st = raw().mlf_aggregate(tab, K, n, kind, op, len(o), wp, _ptr(out), _stream(stream))
+    return _done(st, check)
+
+
+def mlf_apply_ordered(model, momentum, updates, order, lr, mu, n=None, stream=None,
+                      check=True):
+    """Fold h <- mu h - lr g ; w <- w + h over the listed updates, in one pass."""
+    n = model.numel() if n is None else int(n)
+    _state(model, n, "model")
+    _state(momentum, n, "momentum")
+    tab, K, kind, o, op, _, _ = _dense_tables(updates, order, None, n)
+    st = raw().mlf_apply_ordered(_ptr(model), _ptr(momentum), tab, K, n, kind, op, len(o),
+                                 float(lr), float(mu), _stream(stream))
+    return _done(st, check)
+
+
+def mlf_aggregate_apply(model, momentum, out, updates, order, weights, lr, mu, n=None,
+                        stream=None, check=True):
+    """The ordered weighted sum, then one server step with it, fused."""
+    n = model.numel() if n is None else int(n)
+    _state(model, n, "model")
+    _state(momentum, n, "momentum")
+    _state(out, n, "out")
+    tab, K, kind, o, op, w, wp = _dense_tables(updates, order, weights, n)
+    st = raw().mlf_aggregate_apply(_ptr(model), _ptr(momentum), _ptr(out), tab, K, n, kind,
+                                   op, len(o), wp, float(lr), float(mu), _stream(stream))
+    return _done(st, check)
+
+
+def mlf_sparse_workspace_bytes(V, T, total_triples) -> int:
+    return int(raw().mlf_sparse_workspace_bytes(int(V), int(T), int(total_triples)))
+
+
+def mlf_sparse_scatter_add(counts, totals, V, T, triples, workspace=None, n_rejected=None,
+                           stream=None, check=True):
+    """counts[word*T+topic] += delta and totals[topic] += delta for every
+    (word, topic, delta) row of every int32 [m, 3] buffer in ``triples``."""
+    if counts.dtype != torch.int32 or not counts.is_contiguous() or counts.numel() < V * T:
+        raise ValueError("counts must be contiguous int32 with V*T entries")
+    if totals is not None and (totals.dtype != torch.int32 or not totals.is_contiguous()
+                               or totals.numel() < T):
+        raise ValueError("totals must be contiguous int32 with T entries")
+    K = len(triples)
+    tab = (_c.c_void_p * max(K, 1))()
+    cnt = (_c.c_int64 * max(K, 1))()
+    for k, t in enumerate(triples):
+        if t.dtype != torch.int32 or not t.is_contiguous() or t.numel() % 3 != 0:
+            raise ValueError("each triple buffer must be contiguous int32 [m, 3]")
+        tab[k] = _ptr(t)
+        cnt[k] = t.numel() // 3
+    ws_bytes = 0
+    if workspace is not None:
+        ws_bytes = workspace.numel() * workspace.element_size()
+    st = raw().mlf_sparse_scatter_add(_ptr(counts), _ptr(totals), int(V), int(T), tab, cnt, K,
+                                      _ptr(workspace), ws_bytes, _ptr(n_rejected),
+                                      _stream(stream))
+    return _done(st, check)

@@ -1,0 +1,81 @@
+"""Helpers shared by the GPU parity tests: run one call on the GPU library and
+on the CPU oracle from the same seeded inputs and compare raw bits."""
+import numpy as np
+import torch
+
+import oracle
+import paper_1907_00434_amd as mlf
+import workloads as W
+
+ORACLE_THREADS = 16
+
+
+def assert_same_bits(gpu: torch.Tensor, ref: np.ndarray, what: str):
+    """Bit-for-bit equality of binary32 data; any NaN matches any NaN."""
+    got = gpu.detach().cpu().numpy()
+    assert got.shape == ref.shape, what
+    a, b = got.view(np.uint32), ref.view(np.uint32)
+    if np.array_equal(a, b):
+        return
+    bad = (a != b) & ~(np.isnan(got) & np.isnan(ref))
+    if bad.any():
+        i = int(np.flatnonzero(bad)[0])
+        raise AssertionError(
+            f"{what}: {int(bad.sum())} of {bad.size} elements differ; first at {i}: "
+            f"gpu {got[i]!r} (0x{a[i]:08x}) vs oracle {ref[i]!r} (0x{b[i]:08x})")
+
+
+def run_dense(call, d, want_out=False, threads=ORACLE_THREADS):
+    """Runs `call` ("aggregate" | "apply_ordered" | "aggregate_apply") on the
+    device tensors in d and on host copies through the oracle; compares every
+    output bit for bit."""
+    ups_h = [W.to_host(u) if u is not None else None for u in d["updates"]]
+    # the oracle needs an array for every worker; dropped ones are never read
+    filler = next(u for u in ups_h if u is not None)
+    ups_h = [u if u is not None else filler for u in ups_h]
+    order, weights = d["order"], d.get("weights")
+    n = d["updates"][int(order[0])].numel() if len(order) else d["n"]
+    if call == "aggregate":
+        out = torch.full((n,), 7.0, device="cuda")
+        mlf.mlf_aggregate(d["updates"], order, weights, out)
+        ref = oracle.aggregate(ups_h, order, weights, threads=threads)
+        assert_same_bits(out, ref, "aggregate out")
+        return
+    w_h = W.to_host(d["model"])
+    h_h = W.to_host(d["momentum"]) if d["momentum"] is not None else None
+    model = d["model"].clone()
+    momentum = d["momentum"].clone() if d["momentum"] is not None else None
+    if call == "apply_ordered":
+        mlf.mlf_apply_ordered(model, momentum, d["updates"], order, d["lr"], d["mu"])
+        oracle.apply_ordered(w_h, h_h, ups_h, order, d["lr"], d["mu"], threads=threads)
+    else:
+        out = torch.full((n,), 7.0, device="cuda") if want_out else None
+        mlf.mlf_aggregate_apply(model, momentum, out, d["updates"], order, weights,
+                                d["lr"], d["mu"])
+        ref_out = oracle.aggregate_apply(w_h, h_h, ups_h, order, weights, d["lr"], d["mu"],
+                                         want_out=want_out, threads=threads)
+        if want_out:
+            assert_same_bits(out, ref_out, "aggregate_apply out")
+    assert_same_bits(model, w_h, f"{call} model")
+    if momentum is not None:
+        assert_same_bits(momentum, h_h, f"{call} momentum")
+
+
+def run_sparse(cfg, d, use_workspace, threads=ORACLE_THREADS):
+    counts_h, totals_h = W.to_host(d["counts"]), W.to_host(d["totals"])
+    tr_h = [W.to_host(t) for t in d["triples"]]
+    counts, totals = d["counts"].clone(), d["totals"].clone()
+    rejected = torch.zeros(1, dtype=torch.int32, device="cuda")
+    ws = None
+    if use_workspace:
+        total = sum(t.shape[0] for t in d["triples"])
+        nbytes = mlf.mlf_sparse_workspace_bytes(cfg.V, cfg.T, total)
+        ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device="cuda")
+    mlf.mlf_sparse_scatter_add(counts, totals, cfg.V, cfg.T, d["triples"], workspace=ws,
+                               n_rejected=rejected)
+    rej = oracle.scatter_add(counts_h, totals_h, cfg.V, cfg.T, tr_h, threads=threads)
+    torch.cuda.synchronize()
+    assert np.array_equal(counts.cpu().numpy(), counts_h), "counts differ"
+    assert np.array_equal(totals.cpu().numpy(), totals_h), "totals differ"
+    assert int(rejected.item()) == rej, "rejected count differs"
+    return counts, totals

@@ -1,0 +1,118 @@
+"""The C-ABI library loads, exports every symbol the header declares, and its
+host-side argument checks answer without touching a GPU (every call below
+returns before anything is enqueued)."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_1907_00434_amd as mlf
+from paper_1907_00434_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "mlfabric.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(mlf_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported():
+    names = declared_functions()
+    assert {"mlf_aggregate", "mlf_apply_ordered", "mlf_aggregate_apply",
+            "mlf_sparse_scatter_add", "mlf_sparse_workspace_bytes",
+            "mlf_status_string"} <= set(names)
+    lib = ctypes.CDLL(mlf.library_path())
+    for name in names:
+        assert hasattr(lib, name), name
+
+
+def test_status_strings():
+    for code in (0, -1, -2, -3, -4):
+        assert mlf.mlf_status_string(code).startswith("MLF_")
+    assert "unknown" in mlf.mlf_status_string(-99)
+
+
+FAKE = 0x10000000   # stands for a 16-byte aligned device address; never dereferenced
+
+
+def tab(*ptrs):
+    t = (ctypes.c_void_p * len(ptrs))(*ptrs)
+    return t
+
+
+def order(*idx):
+    a = (ctypes.c_int32 * max(len(idx), 1))(*idx)
+    return a, len(idx)
+
+
+def agg(ptrs, K, n, dtype, idx, out, weights=None):
+    o, m = order(*idx)
+    return B.raw().mlf_aggregate(tab(*ptrs), K, n, dtype, o, m, weights, out, None)
+
+
+def test_aggregate_argument_checks():
+    u0, u1, out = FAKE, FAKE + 0x100000, FAKE + 0x200000
+    assert agg([u0, u1], 2, 0, B.MLF_F32, [0, 1], out) == B.MLF_OK          # n = 0
+    assert agg([u0, u1], 0, 8, B.MLF_F32, [], out) == B.MLF_EINVAL          # K < 1
+    assert agg([u0, u1], 2, -1, B.MLF_F32, [0], out) == B.MLF_EINVAL
+    assert agg([u0, u1], 2, 8, B.MLF_F32, [0, 0], out) == B.MLF_EINVAL      # listed twice
+    assert agg([u0, u1], 2, 8, B.MLF_F32, [2], out) == B.MLF_EINVAL         # out of range
+    assert agg([u0, u1], 2, 8, B.MLF_F32, [-1], out) == B.MLF_EINVAL
+    assert agg([u0, u1], 2, 8, B.MLF_F32, [0, 1, 0], out) == B.MLF_EINVAL   # n_order > K
+    assert agg([u0, None], 2, 8, B.MLF_F32, [1], out) == B.MLF_EINVAL       # listed but NULL
+    assert agg([u0, u1], 2, 8, B.MLF_F32, [0], None) == B.MLF_EINVAL        # NULL out
+    assert agg([u0, u1], 2, 8, 7, [0], out) == B.MLF_EINVAL                 # dtype
+    assert agg([u0 + 2, u1], 2, 8, B.MLF_F32, [0], out) == B.MLF_EALIGN
+    assert agg([u0 + 1, u1], 2, 8, B.MLF_BF16, [0], out) == B.MLF_EALIGN
+    assert agg([u0, u1], 2, 8, B.MLF_F32, [0], out + 2) == B.MLF_EALIGN
+    assert agg([u0, u1], 2, 8, B.MLF_F32, [1], u1 + 16) == B.MLF_EINVAL     # out overlaps update
+    assert agg([u0] * 65, 65, 8, B.MLF_F32, [0], out) == B.MLF_EUNSUPPORTED
+
+
+def test_apply_argument_checks():
+    lib = B.raw()
+    u0, w, h = FAKE, FAKE + 0x100000, FAKE + 0x200000
+    o, m = order(0)
+    assert lib.mlf_apply_ordered(None, h, tab(u0), 1, 8, 0, o, m, 0.1, 0.9, None) == B.MLF_EINVAL
+    assert lib.mlf_apply_ordered(w, w + 16, tab(u0), 1, 8, 0, o, m, 0.1, 0.9, None) == B.MLF_EINVAL
+    assert lib.mlf_apply_ordered(w, h, tab(w), 1, 8, 0, o, m, 0.1, 0.9, None) == B.MLF_EINVAL
+    assert lib.mlf_apply_ordered(w, h, tab(u0), 1, 0, 0, o, m, 0.1, 0.9, None) == B.MLF_OK
+    e, _ = order()
+    assert lib.mlf_apply_ordered(w, h, tab(u0), 1, 8, 0, e, 0, 0.1, 0.9, None) == B.MLF_OK
+    assert lib.mlf_aggregate_apply(w, h, w + 4, tab(u0), 1, 8, 0, o, m, None, 0.1, 0.9,
+                                   None) == B.MLF_EINVAL
+    assert lib.mlf_aggregate_apply(None, h, None, tab(u0), 1, 8, 0, o, m, None, 0.1, 0.9,
+                                   None) == B.MLF_EINVAL
+
+
+def test_sparse_argument_checks():
+    lib = B.raw()
+    counts, buf = FAKE, FAKE + 0x100000
+    n1 = (ctypes.c_int64 * 1)(5)
+    n0 = (ctypes.c_int64 * 1)(0)
+    neg = (ctypes.c_int64 * 1)(-1)
+
+    def call(c, V, T, ptrs, cnt, K):
+        return lib.mlf_sparse_scatter_add(c, None, V, T, ptrs, cnt, K, None, 0, None, None)
+
+    assert call(None, 3, 2, tab(buf), n1, 1) == B.MLF_EINVAL
+    assert call(counts, 0, 2, tab(buf), n1, 1) == B.MLF_EINVAL
+    assert call(counts, 3, 0, tab(buf), n1, 1) == B.MLF_EINVAL
+    assert call(counts, 3, 2, tab(buf), neg, 1) == B.MLF_EINVAL
+    assert call(counts, 3, 2, tab(None), n1, 1) == B.MLF_EINVAL
+    assert call(counts, 3, 2, tab(buf + 2), n1, 1) == B.MLF_EALIGN
+    assert call(counts, 3, 2, tab(buf), n0, 1) == B.MLF_OK
+    assert call(counts, 3, 2, None, None, 0) == B.MLF_OK
+    many = (ctypes.c_int64 * 65)(*([1] * 65))
+    assert call(counts, 3, 2, tab(*([buf] * 65)), many, 65) == B.MLF_EUNSUPPORTED
+    assert mlf.mlf_sparse_workspace_bytes(100000, 1000, 0) >= 0
+
+
+def test_binding_refuses_host_tensors():
+    import torch
+    with pytest.raises(ValueError):
+        mlf.mlf_aggregate([torch.zeros(4)], [0], None, torch.zeros(4))
