@@ -19,37 +19,41 @@
 
 #pragma clang fp contract(off)
 
-// Launch shape (compile-time so that sweeps can rebuild with other values).
-#ifndef MLF_VPT_F32      // 128-bit groups per lane and tile, binary32 updates
-#define MLF_VPT_F32 2
+// Launch shapes: lanes per workgroup, groups per lane and tile, and number of
+// updates whose loads are issued before any is consumed.  They are macros so that
+// a sweep can rebuild the library with other values; the defaults are the best
+// of such sweeps on MI355X (small workgroups, 32 loads in flight per lane).
+#ifndef MLF_SHAPE_F32
+#define MLF_SHAPE_F32 64, 2, 16
 #endif
-#ifndef MLF_VPT_BF16     // 128-bit groups (8 elements) per lane and tile, bfloat16
-#define MLF_VPT_BF16 1
+#ifndef MLF_SHAPE_BF16V4      // bfloat16, 4 elements per lane and group
+#define MLF_SHAPE_BF16V4 64, 2, 8
 #endif
-#ifndef MLF_CHUNK        // updates whose loads are issued before any is consumed
-#define MLF_CHUNK 8
+#ifndef MLF_SHAPE_BF16V8      // bfloat16, 8 elements per lane and group
+#define MLF_SHAPE_BF16V8 256, 1, 8
 #endif
-#ifndef MLF_NT_LOAD      // updates are read once: bypass-friendly load hint
-#define MLF_NT_LOAD 1
-#endif
-#ifndef MLF_NT_STORE
-#define MLF_NT_STORE 0
-#endif
-#ifndef MLF_MAX_GRID     // workgroups per launch; tiles beyond it are strided
-#define MLF_MAX_GRID (1 << 20)
+// 0: model / momentum use streaming (no-reuse) accesses only when they are too
+// large to stay in the 256 MiB Infinity Cache between calls; 1: never; 4: always.
+#ifndef MLF_STATE_POLICY
+#define MLF_STATE_POLICY 0
 #endif
 
 namespace {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-
-constexpr int kThreads = 256;
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 enum Op { kAggregate = 0, kAggregateApply = 1, kApplyOrdered = 2 };
 
+// Model + momentum up to this size are left to the caches between calls.
+constexpr long long kInfinityCacheBytes = 256ll << 20;
+// Workgroups that walk the element-wise region (they stride over it).
+constexpr long long kMaxScalarGroups = 4096;
+
 // Kernel argument block.  The host has already applied the scheduler's order:
-// u[t] / wt[t] belong to the t-th committed update.
+// u[t] / wt[t] belong to the t-th committed update (wt = 1 without weights:
+// multiplying by 1 is exact, so the unweighted sum needs no kernel of its own).
 struct DenseArgs {
     const void *u[MLF_MAX_K];
     float wt[MLF_MAX_K];
@@ -58,6 +62,7 @@ struct DenseArgs {
     float *out;
     long long n;            // elements
     long long n_vec;        // leading elements on the 128-bit path (0 if unaligned)
+    unsigned tiles_vec;     // workgroups [0, tiles_vec) each own one 128-bit tile
     int M;                  // committed updates
     float lr;
     float mu;
@@ -67,52 +72,52 @@ struct F32 {
     typedef float elem;
     static constexpr int kVec = 4;      // elements per 128-bit group
 };
-struct BF16 {
+// bfloat16 updates come in two lane layouts.  8 elements per lane: one 128-bit
+// load per update, but a wavefront's 128-bit model / momentum accesses then
+// interleave two to a cache line, which only the cached state policy absorbs.
+// 4 elements per lane: 64-bit update loads, contiguous 128-bit state accesses;
+// the layout for streamed state.
+struct BF16V8 {
     typedef uint16_t elem;
     static constexpr int kVec = 8;
+};
+struct BF16V4 {
+    typedef uint16_t elem;
+    static constexpr int kVec = 4;
 };
 
 __device__ __forceinline__ float from_bits(uint32_t b) { return __uint_as_float(b); }
 
-template <typename T>
-__device__ __forceinline__ T stream_load(const T *p)
-{
-#if MLF_NT_LOAD
-    return __builtin_nontemporal_load(p);
-#else
-    return *p;
-#endif
-}
-
-template <typename T>
-__device__ __forceinline__ void state_store(T *p, T v)
-{
-#if MLF_NT_STORE
-    __builtin_nontemporal_store(v, p);
-#else
-    *p = v;
-#endif
-}
-
-// Load one group of W consecutive update elements, widened to binary32.
-// `e` is the index of the group's first element.
+// Load one group of W consecutive update elements, widened to binary32.  An
+// update is read exactly once, so its loads carry the non-temporal hint and do
+// not displace the model from the caches.  `e` is the group's first element.
 template <typename IN, int W>
 __device__ __forceinline__ void load_update(float (&x)[W], const void *base, long long e)
 {
     if constexpr (W == 1) {
         if constexpr (sizeof(typename IN::elem) == 4) {
-            x[0] = stream_load(static_cast<const float *>(base) + e);
+            x[0] = __builtin_nontemporal_load(static_cast<const float *>(base) + e);
         } else {
-            uint16_t b = stream_load(static_cast<const uint16_t *>(base) + e);
+            uint16_t b = __builtin_nontemporal_load(static_cast<const uint16_t *>(base) + e);
             x[0] = from_bits(static_cast<uint32_t>(b) << 16);
         }
     } else if constexpr (sizeof(typename IN::elem) == 4) {
         static_assert(W == 4, "binary32 groups hold 4 elements");
-        f32x4 v = stream_load(reinterpret_cast<const f32x4 *>(static_cast<const float *>(base) + e));
+        f32x4 v = __builtin_nontemporal_load(
+            reinterpret_cast<const f32x4 *>(static_cast<const float *>(base) + e));
         x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w;
+    } else if constexpr (W == 4) {
+        u32x2 v = __builtin_nontemporal_load(
+            reinterpret_cast<const u32x2 *>(static_cast<const uint16_t *>(base) + e));
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            x[2 * j] = from_bits(v[j] << 16);
+            x[2 * j + 1] = from_bits(v[j] & 0xffff0000u);
+        }
     } else {
-        static_assert(W == 8, "bfloat16 groups hold 8 elements");
-        u32x4 v = stream_load(reinterpret_cast<const u32x4 *>(static_cast<const uint16_t *>(base) + e));
+        static_assert(W == 8, "bfloat16 groups hold 4 or 8 elements");
+        u32x4 v = __builtin_nontemporal_load(
+            reinterpret_cast<const u32x4 *>(static_cast<const uint16_t *>(base) + e));
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             x[2 * j] = from_bits(v[j] << 16);             // low half: even element
@@ -121,7 +126,9 @@ __device__ __forceinline__ void load_update(float (&x)[W], const void *base, lon
     }
 }
 
-template <int W>
+// Model / momentum accesses.  STREAM marks them non-temporal as well: used when
+// the state is too large to stay cached until the next call.
+template <int W, int STREAM>
 __device__ __forceinline__ void load_state(float (&x)[W], const float *base, long long e)
 {
     if constexpr (W == 1) {
@@ -129,13 +136,19 @@ __device__ __forceinline__ void load_state(float (&x)[W], const float *base, lon
     } else {
 #pragma unroll
         for (int j = 0; j < W / 4; ++j) {
-            f32x4 v = *reinterpret_cast<const f32x4 *>(base + e + 4 * j);
+            const f32x4 *p = reinterpret_cast<const f32x4 *>(base + e + 4 * j);
+            f32x4 v;
+            if constexpr ((STREAM & 1) != 0) {
+                v = __builtin_nontemporal_load(p);
+            } else {
+                v = *p;
+            }
             x[4 * j] = v.x; x[4 * j + 1] = v.y; x[4 * j + 2] = v.z; x[4 * j + 3] = v.w;
         }
     }
 }
 
-template <int W>
+template <int W, int STREAM>
 __device__ __forceinline__ void store_state(float *base, long long e, const float (&x)[W])
 {
     if constexpr (W == 1) {
@@ -144,7 +157,12 @@ __device__ __forceinline__ void store_state(float *base, long long e, const floa
 #pragma unroll
         for (int j = 0; j < W / 4; ++j) {
             f32x4 v = {x[4 * j], x[4 * j + 1], x[4 * j + 2], x[4 * j + 3]};
-            state_store(reinterpret_cast<f32x4 *>(base + e + 4 * j), v);
+            f32x4 *p = reinterpret_cast<f32x4 *>(base + e + 4 * j);
+            if constexpr ((STREAM & 2) != 0) {
+                __builtin_nontemporal_store(v, p);
+            } else {
+                *p = v;
+            }
         }
     }
 }
@@ -163,12 +181,13 @@ __device__ __forceinline__ void server_step(float &w, float &h, float g, float l
     }
 }
 
-// Work of one lane on one tile: VPT groups of W elements, kThreads groups apart,
+// Work of one lane on one tile: VPT groups of W elements, THREADS groups apart,
 // so that each load instruction of a wavefront covers one contiguous span.
 //   e0       first element of the region the groups are counted in
 //   g0       this lane's first group in that region
 //   n_groups groups in the region
-template <typename IN, int W, int OP, bool WEIGHTED, bool HAS_H, int VPT, bool FULL>
+template <typename IN, int W, int OP, bool HAS_H, int STREAM, int THREADS, int VPT, int CH,
+          bool FULL>
 struct Tile {
     const DenseArgs &a;
     long long e[VPT];       // first element of each group
@@ -183,7 +202,7 @@ struct Tile {
     {
 #pragma unroll
         for (int v = 0; v < VPT; ++v) {
-            long long g = g0 + static_cast<long long>(v) * kThreads;
+            long long g = g0 + static_cast<long long>(v) * THREADS;
             ok[v] = FULL || g < n_groups;
             e[v] = e0 + g * W;
         }
@@ -219,13 +238,25 @@ struct Tile {
                     if constexpr (OP == kApplyOrdered) {
                         server_step<HAS_H>(w[v][j], h[v][j], x[c][v][j], a.lr, a.mu);
                     } else {
-                        float term = x[c][v][j];
-                        if constexpr (WEIGHTED) term = wt * term;
+                        const float term = wt * x[c][v][j];
                         // The first term starts the sum; later ones are added.
                         acc[v][j] = first ? term : acc[v][j] + term;
                     }
                 }
             }
+        }
+    }
+
+    // Remainder of the sequence in halving pieces; positions stay in order.
+    template <int C>
+    __device__ __forceinline__ void remainder(int &t)
+    {
+        if constexpr (C >= 1) {
+            if (a.M - t >= C) {
+                chunk<C>(t);
+                t += C;
+            }
+            remainder<C / 2>(t);
         }
     }
 
@@ -241,62 +272,59 @@ struct Tile {
             }
             if constexpr (OP != kAggregate) {
                 if (ok[v]) {
-                    load_state<W>(w[v], a.model, e[v]);
-                    if constexpr (HAS_H) load_state<W>(h[v], a.momentum, e[v]);
+                    load_state<W, STREAM>(w[v], a.model, e[v]);
+                    if constexpr (HAS_H) load_state<W, STREAM>(h[v], a.momentum, e[v]);
                 }
             }
         }
 
         int t = 0;
-        for (; t + MLF_CHUNK <= a.M; t += MLF_CHUNK) chunk<MLF_CHUNK>(t);
-        // Remainder in halving pieces; positions stay in sequence order.
-        if constexpr (MLF_CHUNK > 16) { if (a.M - t >= 16) { chunk<16>(t); t += 16; } }
-        if constexpr (MLF_CHUNK > 8) { if (a.M - t >= 8) { chunk<8>(t); t += 8; } }
-        if constexpr (MLF_CHUNK > 4) { if (a.M - t >= 4) { chunk<4>(t); t += 4; } }
-        if constexpr (MLF_CHUNK > 2) { if (a.M - t >= 2) { chunk<2>(t); t += 2; } }
-        if constexpr (MLF_CHUNK > 1) { if (a.M - t >= 1) { chunk<1>(t); t += 1; } }
+        for (; t + CH <= a.M; t += CH) chunk<CH>(t);
+        remainder<CH / 2>(t);
 
 #pragma unroll
         for (int v = 0; v < VPT; ++v) {
             if (!ok[v]) continue;
             if constexpr (OP == kAggregate) {
-                store_state<W>(a.out, e[v], acc[v]);
+                store_state<W, STREAM>(a.out, e[v], acc[v]);
             } else {
                 if constexpr (OP == kAggregateApply) {
 #pragma unroll
                     for (int j = 0; j < W; ++j) {
                         server_step<HAS_H>(w[v][j], h[v][j], acc[v][j], a.lr, a.mu);
                     }
-                    if (a.out != nullptr) store_state<W>(a.out, e[v], acc[v]);
+                    if (a.out != nullptr) store_state<W, STREAM>(a.out, e[v], acc[v]);
                 }
-                store_state<W>(a.model, e[v], w[v]);
-                if constexpr (HAS_H) store_state<W>(a.momentum, e[v], h[v]);
+                store_state<W, STREAM>(a.model, e[v], w[v]);
+                if constexpr (HAS_H) store_state<W, STREAM>(a.momentum, e[v], h[v]);
             }
         }
     }
 };
 
-template <typename IN, int OP, bool WEIGHTED, bool HAS_H, int VPT>
-__global__ __launch_bounds__(kThreads) void dense_kernel(const DenseArgs a)
+// Workgroups [0, tiles_vec) take one tile each of the 128-bit region
+// [0, n_vec); the remaining workgroups stride over the element-wise region
+// [n_vec, n): the ragged tail, or everything when a pointer of the call is not
+// 16-byte aligned.
+template <typename IN, int OP, bool HAS_H, int STREAM, int THREADS, int VPT, int CH>
+__global__ __launch_bounds__(THREADS) void dense_kernel(const DenseArgs a)
 {
     constexpr int WV = IN::kVec;
-    constexpr long long kTile = static_cast<long long>(kThreads) * VPT;
-    const long long stride = static_cast<long long>(gridDim.x) * kTile;
-
-    // 128-bit region: elements [0, n_vec), in groups of WV.
-    const long long groups_v = a.n_vec / WV;
-    for (long long base = blockIdx.x * kTile; base < groups_v; base += stride) {
-        if (base + kTile <= groups_v) {
-            Tile<IN, WV, OP, WEIGHTED, HAS_H, VPT, true>(a, 0, base + threadIdx.x, groups_v).run();
+    constexpr long long kTile = static_cast<long long>(THREADS) * VPT;
+    if (blockIdx.x < a.tiles_vec) {
+        const long long groups = a.n_vec / WV;
+        const long long base = blockIdx.x * kTile;
+        if (base + kTile <= groups) {
+            Tile<IN, WV, OP, HAS_H, STREAM, THREADS, VPT, CH, true>(a, 0, base + threadIdx.x, groups).run();
         } else {
-            Tile<IN, WV, OP, WEIGHTED, HAS_H, VPT, false>(a, 0, base + threadIdx.x, groups_v).run();
+            Tile<IN, WV, OP, HAS_H, STREAM, THREADS, VPT, CH, false>(a, 0, base + threadIdx.x, groups).run();
         }
-    }
-    // Element-wise region: [n_vec, n) -- the ragged tail, or everything when a
-    // pointer of the call is not 16-byte aligned.
-    const long long groups_s = a.n - a.n_vec;
-    for (long long base = blockIdx.x * kTile; base < groups_s; base += stride) {
-        Tile<IN, 1, OP, WEIGHTED, HAS_H, VPT, false>(a, a.n_vec, base + threadIdx.x, groups_s).run();
+    } else {
+        const long long groups = a.n - a.n_vec;
+        const long long stride = static_cast<long long>(gridDim.x - a.tiles_vec) * kTile;
+        for (long long base = (blockIdx.x - a.tiles_vec) * kTile; base < groups; base += stride) {
+            Tile<IN, 1, OP, HAS_H, STREAM, THREADS, VPT, CH, false>(a, a.n_vec, base + threadIdx.x, groups).run();
+        }
     }
 }
 
@@ -316,39 +344,62 @@ Range range_of(const void *p, long long n, size_t elem)
     return Range{lo, lo + static_cast<uintptr_t>(n) * elem};
 }
 
-template <typename IN, int OP, bool WEIGHTED, bool HAS_H>
-mlf_status launch(const DenseArgs &a, hipStream_t stream)
+template <typename IN, int OP, bool HAS_H, int STREAM, int THREADS, int VPT, int CH>
+mlf_status launch_shape(DenseArgs &a, hipStream_t stream)
 {
-    constexpr int VPT = sizeof(typename IN::elem) == 4 ? MLF_VPT_F32 : MLF_VPT_BF16;
-    constexpr long long kTile = static_cast<long long>(kThreads) * VPT;
-    long long tiles_v = (a.n_vec / IN::kVec + kTile - 1) / kTile;
+    constexpr long long kTile = static_cast<long long>(THREADS) * VPT;
+    a.n_vec = a.n_vec / IN::kVec * IN::kVec;    // whole groups only
+    const long long tiles_v = (a.n_vec / IN::kVec + kTile - 1) / kTile;
     long long tiles_s = (a.n - a.n_vec + kTile - 1) / kTile;
-    long long grid = tiles_v > tiles_s ? tiles_v : tiles_s;
-    if (grid < 1) grid = 1;
-    if (grid > MLF_MAX_GRID) grid = MLF_MAX_GRID;
-    dense_kernel<IN, OP, WEIGHTED, HAS_H, VPT>
-        <<<dim3(static_cast<unsigned>(grid)), dim3(kThreads), 0, stream>>>(a);
+    if (tiles_s > kMaxScalarGroups) tiles_s = kMaxScalarGroups;
+    if (tiles_v + tiles_s > 0x7fffffffll) return MLF_EUNSUPPORTED;
+    a.tiles_vec = static_cast<unsigned>(tiles_v);
+    dense_kernel<IN, OP, HAS_H, STREAM, THREADS, VPT, CH>
+        <<<dim3(static_cast<unsigned>(tiles_v + tiles_s)), dim3(THREADS), 0, stream>>>(a);
     return hipGetLastError() == hipSuccess ? MLF_OK : MLF_EHIP;
 }
 
-template <typename IN, int OP>
-mlf_status dispatch(const DenseArgs &a, bool weighted, hipStream_t stream)
+template <typename IN, int OP, bool HAS_H, int STREAM>
+mlf_status launch(DenseArgs &a, hipStream_t stream)
 {
-    const bool has_h = a.momentum != nullptr;
-    if constexpr (OP == kAggregate) {
-        return weighted ? launch<IN, OP, true, false>(a, stream)
-                        : launch<IN, OP, false, false>(a, stream);
-    } else if constexpr (OP == kApplyOrdered) {
-        return has_h ? launch<IN, OP, false, true>(a, stream)
-                     : launch<IN, OP, false, false>(a, stream);
+    if constexpr (sizeof(typename IN::elem) == 4) {
+        return launch_shape<IN, OP, HAS_H, STREAM, MLF_SHAPE_F32>(a, stream);
+    } else if constexpr (IN::kVec == 4) {
+        return launch_shape<IN, OP, HAS_H, STREAM, MLF_SHAPE_BF16V4>(a, stream);
     } else {
-        if (weighted) {
-            return has_h ? launch<IN, OP, true, true>(a, stream)
-                         : launch<IN, OP, true, false>(a, stream);
-        }
-        return has_h ? launch<IN, OP, false, true>(a, stream)
-                     : launch<IN, OP, false, false>(a, stream);
+        return launch_shape<IN, OP, HAS_H, STREAM, MLF_SHAPE_BF16V8>(a, stream);
     }
+}
+
+template <typename IN, int OP, int STREAM>
+mlf_status dispatch_state(DenseArgs &a, hipStream_t stream)
+{
+    if constexpr (OP == kAggregate) {
+        return launch<IN, OP, false, STREAM>(a, stream);
+    } else {
+        return a.momentum != nullptr ? launch<IN, OP, true, STREAM>(a, stream)
+                                     : launch<IN, OP, false, STREAM>(a, stream);
+    }
+}
+
+template <int OP>
+mlf_status dispatch(DenseArgs &a, mlf_dtype dtype, hipStream_t stream)
+{
+    // State that is too large to survive in the Infinity Cache until the next
+    // call is streamed through; smaller state is left cacheable.
+    long long footprint = 0;
+    if (a.model != nullptr) footprint += 4 * a.n;
+    if (a.momentum != nullptr) footprint += 4 * a.n;
+    if (a.out != nullptr) footprint += 4 * a.n;
+    constexpr int kS = MLF_STATE_POLICY >= 2 ? MLF_STATE_POLICY - 1 : 3;
+    const bool streaming = MLF_STATE_POLICY >= 2 ||
+                           (MLF_STATE_POLICY == 0 && footprint > kInfinityCacheBytes);
+    if (dtype == MLF_F32) {
+        return streaming ? dispatch_state<F32, OP, kS>(a, stream)
+                         : dispatch_state<F32, OP, 0>(a, stream);
+    }
+    return streaming ? dispatch_state<BF16V4, OP, kS>(a, stream)
+                     : dispatch_state<BF16V8, OP, 0>(a, stream);
 }
 
 // Validates the arguments shared by the three dense calls and fills `a`.
@@ -392,9 +443,8 @@ mlf_status prepare(DenseArgs &a, const void *const *update_ptrs, int K, long lon
             if (overlap(r, range_of(a.u[t], n, esz))) return MLF_EINVAL;
         }
     }
-    const int vec = dtype == MLF_F32 ? F32::kVec : BF16::kVec;
     a.n = n;
-    a.n_vec = aligned16 ? (n / vec) * vec : 0;
+    a.n_vec = aligned16 ? n : 0;     // rounded down to whole groups at launch
     a.M = n_order;
     return MLF_OK;
 }
@@ -417,8 +467,7 @@ extern "C" mlf_status mlf_aggregate(const void *const *update_ptrs, int K, int64
     a.lr = 0.0f;
     a.mu = 0.0f;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    return dtype == MLF_F32 ? dispatch<F32, kAggregate>(a, weights != nullptr, s)
-                            : dispatch<BF16, kAggregate>(a, weights != nullptr, s);
+    return dispatch<kAggregate>(a, dtype, s);
 }
 
 extern "C" mlf_status mlf_apply_ordered(float *model, float *momentum,
@@ -438,8 +487,7 @@ extern "C" mlf_status mlf_apply_ordered(float *model, float *momentum,
     a.lr = lr;
     a.mu = mu;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    return dtype == MLF_F32 ? dispatch<F32, kApplyOrdered>(a, false, s)
-                            : dispatch<BF16, kApplyOrdered>(a, false, s);
+    return dispatch<kApplyOrdered>(a, dtype, s);
 }
 
 extern "C" mlf_status mlf_aggregate_apply(float *model, float *momentum, float *out_or_null,
@@ -460,8 +508,7 @@ extern "C" mlf_status mlf_aggregate_apply(float *model, float *momentum, float *
     a.lr = lr;
     a.mu = mu;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    return dtype == MLF_F32 ? dispatch<F32, kAggregateApply>(a, weights != nullptr, s)
-                            : dispatch<BF16, kAggregateApply>(a, weights != nullptr, s);
+    return dispatch<kAggregateApply>(a, dtype, s);
 }
 
 extern "C" const char *mlf_status_string(mlf_status status)

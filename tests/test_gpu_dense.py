@@ -79,6 +79,39 @@ def test_misaligned_base_pointers(call, dtype):
         run_dense(call, e, want_out=True)
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_misaligned_large_enough_to_stride(dtype):
+    """The element-wise region is walked by a bounded number of workgroups that
+    stride over it: make it longer than one sweep of them."""
+    n = 700_001
+    cfg = recipe("cfg2", n=n + 1, K=3, dtype=dtype)
+    d = W.dense_inputs(cfg, "cuda", momentum_init="random")
+    d["model"] = d["model"][1:]
+    d["momentum"] = d["momentum"][:n]
+    d["updates"] = [u[:n] for u in d["updates"]]
+    assert d["model"].data_ptr() % 16 != 0
+    for call in CALLS:
+        run_dense(call, d, want_out=True)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_state_larger_than_the_infinity_cache(dtype):
+    """Model + momentum (+ out) above 256 MiB switch the kernels to streamed
+    state accesses (and bfloat16 to its 4-element lane layout); ragged n."""
+    cfg = recipe("cfg3", n=34_000_003, K=3, dtype=dtype)
+    d = W.dense_inputs(cfg, "cuda", momentum_init="random")
+    d["weights"] = np.array([0.5, 0.3, 1.7], np.float32)
+    run_dense("apply_ordered", d)
+    run_dense("aggregate_apply", d, want_out=True)
+    del d
+    cfg = recipe("cfg3", n=68_000_001, K=2, dtype=dtype)
+    d = W.dense_inputs(cfg, "cuda")
+    d["weights"] = np.array([0.7, 1.1], np.float32)
+    run_dense("aggregate", d)
+    del d
+    torch.cuda.empty_cache()
+
+
 def test_without_momentum_buffer_and_without_weights():
     for dtype in ("f32", "bf16"):
         cfg = recipe("cfg1", n=40_001, dtype=dtype)
