@@ -42,6 +42,30 @@ def test_odd_shapes(use_workspace, V, T, K, m):
     run_sparse(cfg, d, use_workspace)
 
 
+@pytest.mark.parametrize("V,T,K,m", [(1, 1, 1, 70_000), (3, 2, 2, 40_000), (32_769, 1, 1, 66_000),
+                                     (1, 32_768, 2, 33_000), (7, 9_363, 3, 30_011),
+                                     (4_099, 8, 1, 200_000), (2_100_000, 1, 2, 70_000),
+                                     (16_385, 2_048, 2, 50_000)])
+def test_binned_path_edge_shapes(V, T, K, m):
+    """Shapes chosen around the binned path's geometry: one tile shared by
+    several workgroups, a matrix that ends just past a tile boundary, many coarse
+    ranges, and batches just above the size where the binned path starts."""
+    assert K * m >= 65_536
+    cfg = recipe(V=V, T=T, K=K, m=m)
+    d = W.sparse_inputs(cfg, "cuda", init="random", n_invalid=7)
+    assert mlf.mlf_sparse_workspace_bytes(V, T, K * m) > 0
+    run_sparse(cfg, d, True)
+
+
+def test_shapes_the_binned_path_declines():
+    # more than 2^29 cells: no scratch is asked for and the direct path serves
+    assert mlf.mlf_sparse_workspace_bytes(70_000, 8_000, 1_000_000) == 0
+    assert mlf.mlf_sparse_workspace_bytes(100, 100, 100) == 0        # tiny batch
+    cfg = recipe(V=70_000, T=8_000, K=1, m=100_000)
+    d = W.sparse_inputs(cfg, "cuda", init="zeros")
+    run_sparse(cfg, d, True)
+
+
 @pytest.mark.parametrize("use_workspace", [False, True])
 def test_hand_case_ragged_buffers_and_optional_arguments(use_workspace, golden):
     g = {k: np.array([int(x) for x in v], dtype=np.int32)
