@@ -34,16 +34,41 @@ constexpr int kThreads = 256;
 constexpr int kMaxLdsTopics = 16384;     // totals privatised in LDS up to 64 KiB
 
 // ---- geometry of the binned path -------------------------------------------
-constexpr int kTileBits = 15;                    // cells per LDS image: 32768 (128 KiB)
+#ifndef MLF_TILE_BITS
+#define MLF_TILE_BITS 15
+#endif
+#ifndef MLF_FINE_BITS
+#define MLF_FINE_BITS 6
+#endif
+#ifndef MLF_ACC_THREADS
+#define MLF_ACC_THREADS 1024
+#endif
+#ifndef MLF_ACC_CHUNK_BITS
+#define MLF_ACC_CHUNK_BITS 16
+#endif
+constexpr int kTileBits = MLF_TILE_BITS;         // log2 of the cells per LDS image
 constexpr uint32_t kTileCells = 1u << kTileBits;
-constexpr int kFineBits = 6;                     // fine tiles per coarse range: 64
+constexpr int kFineBits = MLF_FINE_BITS;         // log2 of the fine tiles per coarse range
 constexpr uint32_t kFinePerCoarse = 1u << kFineBits;
 constexpr uint32_t kMaxCoarse = 256;             // coarse ranges (one counter per lane)
-constexpr uint32_t kMaxTiles = kMaxCoarse * kFinePerCoarse;   // 16384 tiles = 2^29 cells
-constexpr int kPartItems = 16;                   // records per lane in a partition step
-constexpr uint32_t kPartTile = kThreads * kPartItems;          // 4096 records
-constexpr int kAccThreads = 1024;                // lanes of an accumulate workgroup
-constexpr uint32_t kAccChunk = 1u << 16;         // records per accumulate work item
+constexpr uint32_t kMaxTiles = 16384;            // tiles a call may span (LDS histogram, scan)
+#ifndef MLF_PART_THREADS
+#define MLF_PART_THREADS 512
+#endif
+#ifndef MLF_CURSOR_STRIDE
+#define MLF_CURSOR_STRIDE 32
+#endif
+constexpr int kPartThreads = MLF_PART_THREADS;   // lanes of a partition workgroup
+#ifndef MLF_PART_ITEMS
+#define MLF_PART_ITEMS 8
+#endif
+constexpr int kPartItems = MLF_PART_ITEMS;       // records per lane in a partition step
+constexpr uint32_t kPartTile = kPartThreads * kPartItems;      // records per step
+// Output cursors sit this many words apart: every partition step of a range
+// bumps the same cursors, and atomics on one cache line are served one by one.
+constexpr uint32_t kCursorStride = MLF_CURSOR_STRIDE;
+constexpr int kAccThreads = MLF_ACC_THREADS;     // lanes of an accumulate workgroup
+constexpr uint32_t kAccChunk = 1u << MLF_ACC_CHUNK_BITS;   // records per accumulate work item
 constexpr int kScanThreads = 1024;
 constexpr int kScanItems = kMaxTiles / kScanThreads;           // 16
 constexpr long long kMinBinnedTriples = 1 << 16; // below this the direct path is cheaper
@@ -67,8 +92,8 @@ struct Record {
 // Control block of the binned path, carved out of the caller's scratch.
 struct BinPlan {
     uint32_t *hist;               // [n_tiles]   records per tile            (zeroed)
-    uint32_t *coarse_cursor;      // [n_coarse]  records placed so far       (zeroed)
-    uint32_t *fine_cursor;        // [n_tiles]   records placed so far       (zeroed)
+    uint32_t *coarse_cursor;      // [n_coarse * kCursorStride] records placed so far (zeroed)
+    uint32_t *fine_cursor;        // [n_tiles * kCursorStride]  records placed so far (zeroed)
     uint32_t *tile_start;         // [n_tiles+1] exclusive scan of hist
     uint32_t *coarse_part_start;  // [n_coarse+1] partition steps before each coarse range
     uint32_t *chunk_start;        // [n_tiles+1] accumulate work items before each tile
@@ -97,6 +122,52 @@ __device__ __forceinline__ uint32_t lds_fetch_add(uint32_t *p, uint32_t v)
 __device__ __forceinline__ void lds_add(int32_t *p, int32_t v)
 {
     __hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+}
+
+// Number of lanes below the caller whose bit is set in `mask`.
+__device__ __forceinline__ uint32_t lanes_below(unsigned long long mask)
+{
+    return __builtin_amdgcn_mbcnt_hi(static_cast<uint32_t>(mask >> 32),
+                                     __builtin_amdgcn_mbcnt_lo(static_cast<uint32_t>(mask), 0u));
+}
+
+// counter[bin] += 1 for every live lane, returning to each the value it would
+// have seen had the lanes gone one by one (its rank in the bin).  Skewed data
+// puts most lanes of a wavefront into one bin, and LDS atomics on one address
+// are served one lane at a time; so the lanes that share the bin of the first
+// live lane are counted with a ballot and added by a single atomic, and only
+// the others go one by one.  Must be called by whole wavefronts.
+__device__ __forceinline__ uint32_t wave_rank(uint32_t *counter, uint32_t bin, bool live)
+{
+    const unsigned long long live_mask = __ballot(live);
+    if (live_mask == 0) return 0;                                   // uniform
+    const int leader = __ffsll(static_cast<long long>(live_mask)) - 1;
+    const uint32_t lead_bin = __shfl(bin, leader, 64);
+    const bool grouped = live && bin == lead_bin;
+    const unsigned long long group = __ballot(grouped);
+    uint32_t base = 0;
+    if (static_cast<int>(threadIdx.x & 63) == leader) {
+        base = lds_fetch_add(&counter[lead_bin], static_cast<uint32_t>(__popcll(group)));
+    }
+    base = __shfl(base, leader, 64);
+    if (grouped) return base + lanes_below(group);
+    return live ? lds_fetch_add(&counter[bin], 1u) : 0u;
+}
+
+// counter[bin] += 1 for every active lane, with the same grouping of the lanes
+// that share the first active lane's bin; no value is returned.
+__device__ __forceinline__ void wave_count(uint32_t *counter, uint32_t bin)
+{
+    const unsigned long long active = __ballot(true);
+    const int leader = __ffsll(static_cast<long long>(active)) - 1;
+    const uint32_t lead_bin = __shfl(bin, leader, 64);
+    const bool grouped = bin == lead_bin;
+    const unsigned long long group = __ballot(grouped);
+    if (static_cast<int>(threadIdx.x & 63) == leader) {
+        lds_fetch_add(&counter[lead_bin], static_cast<uint32_t>(__popcll(group)));
+    } else if (!grouped) {
+        lds_fetch_add(&counter[bin], 1u);
+    }
 }
 
 // Reads triple r of a buffer (read once: streaming loads) and tells whether
@@ -147,7 +218,7 @@ __global__ __launch_bounds__(kThreads) void scan_triples_kernel(const SparseArgs
         }
         const long long cell = static_cast<long long>(word) * T + topic;
         if constexpr (BINNED) {
-            lds_fetch_add(&lds_hist[static_cast<uint32_t>(cell) >> kTileBits], 1u);
+            wave_count(lds_hist, static_cast<uint32_t>(cell) >> kTileBits);
         } else {
             add_relaxed(a.counts + cell, delta);
         }
@@ -269,7 +340,7 @@ __device__ __forceinline__ uint32_t owner_of(const uint32_t *start, uint32_t n, 
 }
 
 // One partition step of a workgroup: up to kPartTile records held in registers
-// are grouped by `digit` (n_digits <= kThreads) in LDS and written out so that
+// are grouped by `digit` (n_digits <= kMaxCoarse) in LDS and written out so that
 // the records of one digit form one contiguous run at the place reserved for
 // them in the output.
 //   rec[i], live[i]  the lane's records and whether each exists
@@ -277,9 +348,10 @@ __device__ __forceinline__ uint32_t owner_of(const uint32_t *start, uint32_t n, 
 //   reserve(d, n)    output index where this step's n records of digit d go
 struct PartitionLds {
     Record stage[kPartTile];
-    uint32_t count[kThreads];
-    uint32_t offset[kThreads];
-    uint32_t dest[kThreads];
+    uint32_t count[kMaxCoarse];
+    uint32_t offset[kMaxCoarse];
+    uint32_t dest[kMaxCoarse];
+    uint32_t total;
 };
 
 template <typename DigitOf, typename Reserve>
@@ -287,35 +359,51 @@ __device__ __forceinline__ void partition_step(PartitionLds &s, const Record (&r
                                                const bool (&live)[kPartItems], uint32_t n_digits,
                                                DigitOf digit_of, Reserve reserve, Record *out)
 {
-    s.count[threadIdx.x] = 0;
+    static_assert(kMaxCoarse == 256 && kPartThreads >= 256, "one wavefront scans 4 digits per lane");
+    if (threadIdx.x < kMaxCoarse) s.count[threadIdx.x] = 0;
     __syncthreads();
     uint32_t rank[kPartItems];
 #pragma unroll
     for (int i = 0; i < kPartItems; ++i) {
-        rank[i] = live[i] ? lds_fetch_add(&s.count[digit_of(rec[i].cell)], 1u) : 0u;
+        rank[i] = wave_rank(s.count, digit_of(rec[i].cell), live[i]);
     }
     __syncthreads();
-    // Exclusive scan of the digit counts: one digit per lane.
-    const uint32_t mine = threadIdx.x < n_digits ? s.count[threadIdx.x] : 0u;
-    s.offset[threadIdx.x] = mine;
-    __syncthreads();
-    for (int off = 1; off < kThreads; off <<= 1) {
-        const uint32_t add = threadIdx.x >= static_cast<uint32_t>(off) ? s.offset[threadIdx.x - off] : 0u;
-        __syncthreads();
-        s.offset[threadIdx.x] += add;
-        __syncthreads();
+    if (threadIdx.x < 64) {
+        // Exclusive scan of the 256 digit counts by one wavefront: 4 per lane,
+        // then a shuffle scan of the lane sums.
+        const uint32_t lane = threadIdx.x;
+        uint32_t c[4];
+        uint32_t sum = 0;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            c[k] = s.count[4 * lane + k];
+            sum += c[k];
+        }
+        uint32_t incl = sum;
+        for (int off = 1; off < 64; off <<= 1) {
+            const uint32_t up = __shfl_up(incl, off, 64);
+            if (lane >= static_cast<uint32_t>(off)) incl += up;
+        }
+        uint32_t run = incl - sum;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            s.offset[4 * lane + k] = run;
+            run += c[k];
+        }
+        if (lane == 63) s.total = incl;
     }
-    const uint32_t total = s.offset[kThreads - 1];
-    __syncthreads();
-    s.offset[threadIdx.x] -= mine;                      // inclusive -> exclusive
-    if (mine != 0) s.dest[threadIdx.x] = reserve(threadIdx.x, mine);
+    if (threadIdx.x < n_digits) {
+        const uint32_t mine = s.count[threadIdx.x];
+        if (mine != 0) s.dest[threadIdx.x] = reserve(threadIdx.x, mine);
+    }
     __syncthreads();
 #pragma unroll
     for (int i = 0; i < kPartItems; ++i) {
         if (live[i]) s.stage[s.offset[digit_of(rec[i].cell)] + rank[i]] = rec[i];
     }
     __syncthreads();
-    for (uint32_t i = threadIdx.x; i < total; i += kThreads) {
+    const uint32_t total = s.total;
+    for (uint32_t i = threadIdx.x; i < total; i += kPartThreads) {
         const Record r = s.stage[i];
         const uint32_t d = digit_of(r.cell);
         out[s.dest[d] + (i - s.offset[d])] = r;
@@ -324,7 +412,7 @@ __device__ __forceinline__ void partition_step(PartitionLds &s, const Record (&r
 
 // Coarse partition: blockIdx.y = worker buffer, blockIdx.x = step within it.
 // Valid triples become records in plan.tmp, grouped by coarse range.
-__global__ __launch_bounds__(kThreads) void coarse_partition_kernel(const SparseArgs a,
+__global__ __launch_bounds__(kPartThreads) void coarse_partition_kernel(const SparseArgs a,
                                                                     const BinPlan plan)
 {
     __shared__ PartitionLds s;
@@ -336,7 +424,7 @@ __global__ __launch_bounds__(kThreads) void coarse_partition_kernel(const Sparse
     bool live[kPartItems];
 #pragma unroll
     for (int i = 0; i < kPartItems; ++i) {
-        const long long r = base + i * kThreads + threadIdx.x;
+        const long long r = base + i * kPartThreads + threadIdx.x;
         int word = 0, topic = 0, delta = 0;
         live[i] = r < m && load_triple(tr, r, a.V, a.T, word, topic, delta);
         rec[i].cell = static_cast<uint32_t>(static_cast<long long>(word) * a.T + topic);
@@ -348,14 +436,14 @@ __global__ __launch_bounds__(kThreads) void coarse_partition_kernel(const Sparse
         s, rec, live, plan.n_coarse,
         [](uint32_t cell) { return cell >> (kTileBits + kFineBits); },
         [=](uint32_t c, uint32_t n) {
-            return tile_start[c << kFineBits] + fetch_add_relaxed(cursor + c, n);
+            return tile_start[c << kFineBits] + fetch_add_relaxed(cursor + c * kCursorStride, n);
         },
         plan.tmp);
 }
 
 // Fine partition: workgroup g takes one step of one coarse range of plan.tmp
 // and writes its records to plan.sorted, grouped by tile.
-__global__ __launch_bounds__(kThreads) void fine_partition_kernel(const BinPlan plan)
+__global__ __launch_bounds__(kPartThreads) void fine_partition_kernel(const BinPlan plan)
 {
     __shared__ PartitionLds s;
     __shared__ uint32_t s_coarse;
@@ -372,7 +460,7 @@ __global__ __launch_bounds__(kThreads) void fine_partition_kernel(const BinPlan 
     bool live[kPartItems];
 #pragma unroll
     for (int i = 0; i < kPartItems; ++i) {
-        const uint32_t r = begin + i * kThreads + threadIdx.x;
+        const uint32_t r = begin + i * kPartThreads + threadIdx.x;
         live[i] = r < end;
         rec[i] = live[i] ? plan.tmp[r] : Record{0u, 0};
     }
@@ -383,43 +471,78 @@ __global__ __launch_bounds__(kThreads) void fine_partition_kernel(const BinPlan 
         [](uint32_t cell) { return (cell >> kTileBits) & (kFinePerCoarse - 1); },
         [=](uint32_t f, uint32_t n) {
             const uint32_t tile = first_tile + f;
-            return tile_start[tile] + fetch_add_relaxed(cursor + tile, n);
+            return tile_start[tile] + fetch_add_relaxed(cursor + tile * kCursorStride, n);
         },
         plan.sorted);
 }
 
 // Accumulate: workgroup g takes up to kAccChunk records of one tile, sums them
 // into a private LDS image of the tile and merges the image into counts[].
-__global__ __launch_bounds__(kAccThreads) void accumulate_kernel(int32_t *counts,
+typedef int32_t i32x4 __attribute__((ext_vector_type(4)));
+constexpr int kAccUnroll = 8;                    // record loads in flight per lane
+
+__global__ __launch_bounds__(kAccThreads) void accumulate_kernel(int32_t *__restrict__ counts,
                                                                  const BinPlan plan)
 {
-    __shared__ int32_t image[kTileCells];
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    constexpr int kGroupsPerLane = kTileCells / 4 / kAccThreads;
+    __shared__ __attribute__((aligned(16))) int32_t image[kTileCells];
     __shared__ uint32_t s_tile;
     const uint32_t g = blockIdx.x;
     if (g >= plan.chunk_start[plan.n_tiles]) return;          // uniform
     if (threadIdx.x == 0) s_tile = owner_of(plan.chunk_start, plan.n_tiles, g);
-    for (uint32_t i = threadIdx.x; i < kTileCells; i += kAccThreads) image[i] = 0;
+    i32x4 *image4 = reinterpret_cast<i32x4 *>(image);
+#pragma unroll
+    for (int k = 0; k < kGroupsPerLane; ++k) image4[k * kAccThreads + threadIdx.x] = i32x4{0, 0, 0, 0};
     __syncthreads();
     const uint32_t tile = s_tile;
     const uint32_t chunks = plan.chunk_start[tile + 1] - plan.chunk_start[tile];
     const uint32_t begin = plan.tile_start[tile] + (g - plan.chunk_start[tile]) * kAccChunk;
     const uint32_t end = min(begin + kAccChunk, plan.tile_start[tile + 1]);
-    for (uint32_t r = begin + threadIdx.x; r < end; r += kAccThreads) {
-        const Record rec = plan.sorted[r];
-        lds_add(&image[rec.cell & (kTileCells - 1)], rec.delta);
+    const Record *__restrict__ src = plan.sorted;
+    for (uint32_t r0 = begin + threadIdx.x; r0 < end; r0 += kAccThreads * kAccUnroll) {
+        Record rec[kAccUnroll];
+#pragma unroll
+        for (int u = 0; u < kAccUnroll; ++u) {
+            const uint32_t r = r0 + u * kAccThreads;
+            rec[u] = r < end ? src[r] : Record{0u, 0};
+        }
+#pragma unroll
+        for (int u = 0; u < kAccUnroll; ++u) {
+            if (r0 + u * kAccThreads < end) lds_add(&image[rec[u].cell & (kTileCells - 1)], rec[u].delta);
+        }
     }
     __syncthreads();
     const unsigned long long base = static_cast<unsigned long long>(tile) << kTileBits;
     const unsigned long long left = plan.n_cells - base;
     const uint32_t cells = left < kTileCells ? static_cast<uint32_t>(left) : kTileCells;
-    int32_t *dst = counts + base;
+    int32_t *__restrict__ dst = counts + base;
+    // 128-bit groups where the destination allows it, single cells otherwise.
+    const uint32_t groups = reinterpret_cast<uintptr_t>(dst) % 16 == 0 ? cells / 4 : 0;
     if (chunks == 1) {
-        // This workgroup is the only writer of the tile: plain read-modify-write.
-        for (uint32_t i = threadIdx.x; i < cells; i += kAccThreads) {
+        // This workgroup is the only writer of the tile: plain read-modify-write
+        // (int32 addition wraps; done on unsigned values).  All loads of a lane
+        // are issued before its first store, so their latencies overlap.
+        u32x4 *dst4 = reinterpret_cast<u32x4 *>(dst);
+        u32x4 add[kGroupsPerLane], old[kGroupsPerLane];
+        bool touch[kGroupsPerLane];
+#pragma unroll
+        for (int k = 0; k < kGroupsPerLane; ++k) {
+            const uint32_t i = k * kAccThreads + threadIdx.x;
+            add[k] = __builtin_bit_cast(u32x4, image4[i]);
+            touch[k] = i < groups && (add[k].x | add[k].y | add[k].z | add[k].w) != 0;
+            old[k] = touch[k] ? dst4[i] : u32x4{0, 0, 0, 0};
+        }
+#pragma unroll
+        for (int k = 0; k < kGroupsPerLane; ++k) {
+            if (touch[k]) dst4[k * kAccThreads + threadIdx.x] = old[k] + add[k];
+        }
+        for (uint32_t i = groups * 4 + threadIdx.x; i < cells; i += kAccThreads) {
             const int32_t v = image[i];
             if (v != 0) dst[i] = static_cast<int32_t>(static_cast<uint32_t>(dst[i]) + static_cast<uint32_t>(v));
         }
     } else {
+        // Shared tile: lane i adds cell i, so a wavefront's atomics are contiguous.
         for (uint32_t i = threadIdx.x; i < cells; i += kAccThreads) {
             const int32_t v = image[i];
             if (v != 0) add_relaxed(dst + i, v);
@@ -433,6 +556,11 @@ __global__ __launch_bounds__(kAccThreads) void accumulate_kernel(int32_t *counts
 
 size_t align_up(size_t x) { return (x + 255) & ~static_cast<size_t>(255); }
 
+// Upper bounds of the work lists the plan kernel builds on the device: the sum
+// over ranges of ceil(n_r / step) is at most n / step + number of ranges.
+size_t max_fine_steps(long long n, uint32_t n_coarse) { return static_cast<size_t>(n / kPartTile) + n_coarse; }
+size_t max_acc_items(long long n, uint32_t n_tiles) { return static_cast<size_t>(n / kAccChunk) + n_tiles; }
+
 // Whether the binned path can serve this shape, and its scratch layout.
 // Returns the scratch size in bytes (0 when the shape is not eligible).
 size_t plan_layout(int32_t V, int32_t T, long long n, char *ws, BinPlan *plan)
@@ -443,6 +571,7 @@ size_t plan_layout(int32_t V, int32_t T, long long n, char *ws, BinPlan *plan)
     if (tiles > kMaxTiles) return 0;
     const uint32_t n_tiles = static_cast<uint32_t>(tiles);
     const uint32_t n_coarse = (n_tiles + kFinePerCoarse - 1) >> kFineBits;
+    if (n_coarse > kMaxCoarse) return 0;
     size_t off = 0;
     auto take = [&](size_t bytes) {
         char *p = ws != nullptr ? ws + off : nullptr;
@@ -450,7 +579,8 @@ size_t plan_layout(int32_t V, int32_t T, long long n, char *ws, BinPlan *plan)
         return p;
     };
     // hist, coarse_cursor, fine_cursor are contiguous: cleared by one kernel.
-    char *hist = take(sizeof(uint32_t) * (2 * static_cast<size_t>(n_tiles) + n_coarse));
+    const size_t n_zeroed = n_tiles + static_cast<size_t>(kCursorStride) * (n_coarse + n_tiles);
+    char *hist = take(sizeof(uint32_t) * n_zeroed);
     char *tile_start = take(sizeof(uint32_t) * (n_tiles + 1));
     char *coarse_part_start = take(sizeof(uint32_t) * (n_coarse + 1));
     char *chunk_start = take(sizeof(uint32_t) * (n_tiles + 1));
@@ -459,7 +589,7 @@ size_t plan_layout(int32_t V, int32_t T, long long n, char *ws, BinPlan *plan)
     if (plan != nullptr) {
         plan->hist = reinterpret_cast<uint32_t *>(hist);
         plan->coarse_cursor = plan->hist + n_tiles;
-        plan->fine_cursor = plan->coarse_cursor + n_coarse;
+        plan->fine_cursor = plan->coarse_cursor + static_cast<size_t>(kCursorStride) * n_coarse;
         plan->tile_start = reinterpret_cast<uint32_t *>(tile_start);
         plan->coarse_part_start = reinterpret_cast<uint32_t *>(coarse_part_start);
         plan->chunk_start = reinterpret_cast<uint32_t *>(chunk_start);
@@ -547,7 +677,7 @@ extern "C" mlf_status mlf_sparse_scatter_add(int32_t *counts, int32_t *totals, i
 
     // 1. clear the counters, 2. histogram (+ totals, rejects), 3. offsets,
     // 4. coarse partition, 5. fine partition, 6. accumulate and merge.
-    const uint32_t n_clear = 2 * plan.n_tiles + plan.n_coarse;
+    const uint32_t n_clear = plan.n_tiles + kCursorStride * (plan.n_coarse + plan.n_tiles);
     clear_kernel<<<dim3((n_clear + kThreads - 1) / kThreads), dim3(kThreads), 0, s>>>(plan.hist, n_clear);
     if (!launched()) return MLF_EHIP;
     const size_t hist_lds = static_cast<size_t>(plan.n_tiles) * sizeof(uint32_t);
@@ -564,14 +694,12 @@ extern "C" mlf_status mlf_sparse_scatter_add(int32_t *counts, int32_t *totals, i
     plan_kernel<<<dim3(1), dim3(kScanThreads), 0, s>>>(plan);
     if (!launched()) return MLF_EHIP;
     const unsigned steps_per_buffer = static_cast<unsigned>((longest + kPartTile - 1) / kPartTile);
-    coarse_partition_kernel<<<dim3(steps_per_buffer, static_cast<unsigned>(used)), dim3(kThreads), 0, s>>>(a, plan);
+    coarse_partition_kernel<<<dim3(steps_per_buffer, static_cast<unsigned>(used)), dim3(kPartThreads), 0, s>>>(a, plan);
     if (!launched()) return MLF_EHIP;
-    // Upper bounds of the work lists the plan kernel builds on the device:
-    // ceil(n_c / tile) summed over ranges <= n / tile + number of ranges.
-    const unsigned fine_steps = static_cast<unsigned>(total / kPartTile) + plan.n_coarse;
-    fine_partition_kernel<<<dim3(fine_steps), dim3(kThreads), 0, s>>>(plan);
+    const unsigned fine_steps = static_cast<unsigned>(max_fine_steps(total, plan.n_coarse));
+    fine_partition_kernel<<<dim3(fine_steps), dim3(kPartThreads), 0, s>>>(plan);
     if (!launched()) return MLF_EHIP;
-    const unsigned acc_items = static_cast<unsigned>(total / kAccChunk) + plan.n_tiles;
+    const unsigned acc_items = static_cast<unsigned>(max_acc_items(total, plan.n_tiles));
     accumulate_kernel<<<dim3(acc_items), dim3(kAccThreads), 0, s>>>(counts, plan);
     return launched() ? MLF_OK : MLF_EHIP;
 }
