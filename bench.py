@@ -25,6 +25,17 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
 
+# HBM bytes per launch from hardware counters (FETCH_SIZE x 2.000 + WRITE_SIZE x
+# 1.000, the factors a plain 1 GiB copy calibrates), taken with the kernels as
+# they are in this tree; see profiles/hbm_traffic_pmc.md.  cfg5 = whole call.
+MEASURED_TRAFFIC_BYTES = {
+    "cfg1": 25.2e6,
+    "cfg2": 2044.7e6,
+    "cfg3": 8798.6e6,
+    "cfg4": 4427.5e6,
+    "cfg5": 4319.0e6,
+}
+
 
 def parse_args():
     ap = argparse.ArgumentParser()
@@ -216,7 +227,7 @@ def main():
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": round(achieved / HBM_PEAK_GBS, 4),
-            "traffic": None,
+            "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload),
             "kernel": job.kernel,
             "avg_launch_ms": round(event_ms, 5),
         },
