@@ -27,7 +27,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
 
 # HBM bytes per launch from hardware counters (FETCH_SIZE x 2.000 + WRITE_SIZE x
 # 1.000, the factors a plain 1 GiB copy calibrates), taken with the kernels as
-# they are in this tree; see profiles/hbm_traffic_pmc.md.  cfg5 = whole call.
+# they are in this tree (summary kept under profiles/).  cfg5 = whole call.
 MEASURED_TRAFFIC_BYTES = {
     "cfg1": 25.2e6,
     "cfg2": 2044.7e6,

@@ -66,8 +66,8 @@ typedef void *mlf_stream;   /* a hipStream_t */
  *
  * summed left to right in that order; each product is rounded, then each sum.
  * The first term starts the accumulator (no "0 +").  weights == NULL means all
- * weights are 1 and no multiply is done.  n_order == 0 writes +0 everywhere;
- * n == 0 does nothing.
+ * weights are 1 (multiplying by 1 is exact, so the result is the plain ordered
+ * sum).  n_order == 0 writes +0 everywhere; n == 0 does nothing.
  *
  *   update_ptrs  host   K device pointers, one vector of n elements per worker
  *   order        host   n_order indices (may be NULL when n_order == 0)
@@ -141,15 +141,19 @@ mlf_status mlf_aggregate_apply(float *model, float *momentum, float *out_or_null
  *   n_triples     host   K counts (>= 0)
  *   workspace     device scratch of at least
  *                        mlf_sparse_workspace_bytes(V, T, total) bytes, 256-byte
- *                        aligned, contents undefined before and after; with NULL
- *                        (or fewer bytes) the call takes the direct path, which
- *                        needs none and gives the same result
+ *                        aligned, contents undefined before and after.  With it
+ *                        the triples are first grouped by the 128 KiB tile of
+ *                        counts[] they hit (several times faster for large
+ *                        batches); with NULL (or fewer bytes, or a shape that
+ *                        path does not serve) the call takes the direct path,
+ *                        which needs none and gives the same result
  *   n_rejected    device int32 counter that the call ADDS to (the caller clears
  *                        it), or NULL
  *
- * MLF_EINVAL: V < 1, T < 1, V*T >= 2^31 * 2^31 (overflow), K < 0, a negative
- * count, a NULL buffer with a positive count, NULL counts.  K == 0 or no
- * triples does nothing.  MLF_EUNSUPPORTED: K > MLF_MAX_K.
+ * MLF_EINVAL: V < 1, T < 1, K < 0, a negative count, a NULL buffer with a
+ * positive count, NULL counts.  K == 0 or no triples does nothing.
+ * MLF_EUNSUPPORTED: K > MLF_MAX_K.  The triple buffers must not change between
+ * the call and the completion of its work on the stream.
  */
 mlf_status mlf_sparse_scatter_add(int32_t *counts, int32_t *totals, int32_t V,
                                   int32_t T, const int32_t *const *triple_ptrs,
@@ -157,8 +161,9 @@ mlf_status mlf_sparse_scatter_add(int32_t *counts, int32_t *totals, int32_t V,
                                   void *workspace, size_t workspace_bytes,
                                   int32_t *n_rejected, mlf_stream stream);
 
-/* Scratch the binned path of mlf_sparse_scatter_add needs for this problem
- * size (0 when that path would not be used). */
+/* Scratch the grouped path of mlf_sparse_scatter_add needs for this problem
+ * size: about 16 bytes per triple.  0 when that path would not be used: fewer
+ * than 65,536 triples, or a matrix of more than 2^29 cells. */
 size_t mlf_sparse_workspace_bytes(int32_t V, int32_t T, int64_t total_triples);
 
 /* Static, human-readable name of a status code. */
