@@ -60,6 +60,10 @@ def _load():
         f.argtypes = [c.c_void_p, c.c_void_p, c.c_void_p, pp, c.c_int,
                       c.c_int64, i32p, c.c_int, f32p, c.c_float, c.c_float]
         f.restype = None
+        f = getattr(lib, f"orc_apply_grouped_{dt}")
+        f.argtypes = [c.c_void_p, c.c_void_p, pp, c.c_int, c.c_int64, i32p, c.c_int,
+                      f32p, i32p, c.c_int, c.c_float, c.c_float]
+        f.restype = None
     lib.orc_scatter_add.argtypes = [c.c_void_p, c.c_void_p, c.c_int32,
                                     c.c_int32, pp, c.POINTER(c.c_int64),
                                     c.c_int, c.c_int32, c.c_int32, c.c_int32,
@@ -206,6 +210,34 @@ def aggregate_apply(model, momentum, updates, order, weights, lr, mu,
 
     _run([job(lo, hi) for lo, hi in _slices(n, threads)], threads)
     return out
+
+
+def apply_grouped(model, momentum, updates, order, weights, group_len, lr, mu, threads=1):
+    """One scheduled batch: consecutive groups of the order, each summed (ordered,
+    weighted) and applied as one server step; in place."""
+    lib = _load()
+    kind, size, n = _dense_kind(updates)
+    K = len(updates)
+    o = _order_array(order, K)
+    w = _weights_array(weights, K)
+    g = np.ascontiguousarray(np.asarray(group_len, dtype=np.int32))
+    if g.ndim != 1 or (len(g) and g.min() < 1) or int(g.sum()) != len(o):
+        raise ValueError("group lengths must be positive and add up to len(order)")
+    _f32_inplace(model, "model", n)
+    if momentum is not None:
+        _f32_inplace(momentum, "momentum", n)
+    fn = getattr(lib, f"orc_apply_grouped_{kind}")
+    op = o.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
+    gp = g.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
+    wp = w.ctypes.data_as(ctypes.POINTER(ctypes.c_float)) if w is not None else None
+
+    def job(lo, hi):
+        tab = _ptr_table(updates, lo * size)
+        hp = momentum.ctypes.data + 4 * lo if momentum is not None else None
+        return lambda: fn(model.ctypes.data + 4 * lo, hp, tab, K, hi - lo, op, len(o), wp,
+                          gp, len(g), float(lr), float(mu))
+
+    _run([job(lo, hi) for lo, hi in _slices(n, threads)], threads)
 
 
 def scatter_add(counts, totals, V, T, triples, threads=1):

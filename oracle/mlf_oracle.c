@@ -33,6 +33,10 @@
  *  - orc_aggregate_apply_* Sec. 5.4 "Synchronous SGD/PS": the updates of one
  *                          iteration are aggregated and the aggregate is applied
  *                          to the model once (one step of Eq. 2 with g = sum).
+ *  - orc_apply_grouped_*   Sec. 5.2 "Aggregation": a batch reaches the server as a
+ *                          directly forwarded prefix followed by groups that
+ *                          were summed at aggregators; each arrival is one step
+ *                          of Eq. 2.
  *  - orc_scatter_add       Sec. 6 "Datasets and ML models": an LDA worker's
  *                          update is a numerical update to the word-topic count
  *                          matrix; here it arrives as (word, topic, delta)
@@ -217,6 +221,62 @@ void orc_aggregate_apply_bf16(float *model, float *momentum, float *out,
         float w = model[i];
         float h = momentum ? momentum[i] : 0.0f;
         server_step(&w, &h, momentum != NULL, a, lr, mu);
+        model[i] = w;
+        if (momentum) {
+            momentum[i] = h;
+        }
+    }
+}
+
+/* ------------------------------------------------------------------------ */
+/* One scheduled batch as it reaches the server (Sec. 5.2 "Aggregation"): the  */
+/* ordered updates are cut into consecutive groups; the first group goes to    */
+/* the server directly (every update applied on its own: groups of length 1),  */
+/* each later group is summed at an aggregator and arrives as ONE update.      */
+/* Group j covers the next group_len[j] entries of `order`; for each group, in */
+/* sequence:  a = ordered weighted sum of the group ; one step of Eq. 2 with   */
+/* g = a.  The lengths are positive and add up to M.                           */
+/* ------------------------------------------------------------------------ */
+void orc_apply_grouped_f32(float *model, float *momentum, const float *const *U,
+                           int K, int64_t n, const int32_t *order, int M,
+                           const float *weights, const int32_t *group_len,
+                           int n_groups, float lr, float mu)
+{
+    (void)K;
+    (void)M;
+    for (int64_t i = 0; i < n; ++i) {
+        float w = model[i];
+        float h = momentum ? momentum[i] : 0.0f;
+        int first = 0;
+        for (int j = 0; j < n_groups; ++j) {
+            float a = ordered_sum_f32(U, i, order + first, group_len[j], weights);
+            server_step(&w, &h, momentum != NULL, a, lr, mu);
+            first += group_len[j];
+        }
+        model[i] = w;
+        if (momentum) {
+            momentum[i] = h;
+        }
+    }
+}
+
+void orc_apply_grouped_bf16(float *model, float *momentum,
+                            const uint16_t *const *U, int K, int64_t n,
+                            const int32_t *order, int M, const float *weights,
+                            const int32_t *group_len, int n_groups, float lr,
+                            float mu)
+{
+    (void)K;
+    (void)M;
+    for (int64_t i = 0; i < n; ++i) {
+        float w = model[i];
+        float h = momentum ? momentum[i] : 0.0f;
+        int first = 0;
+        for (int j = 0; j < n_groups; ++j) {
+            float a = ordered_sum_bf16(U, i, order + first, group_len[j], weights);
+            server_step(&w, &h, momentum != NULL, a, lr, mu);
+            first += group_len[j];
+        }
         model[i] = w;
         if (momentum) {
             momentum[i] = h;

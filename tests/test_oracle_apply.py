@@ -218,3 +218,81 @@ def test_aggregate_apply_with_empty_order_takes_a_zero_gradient_step():
     w, h = arr(1.0), arr(0.5)
     out = oracle.aggregate_apply(w, h, [arr(3.0)], [], None, 0.1, 0.5, want_out=True)
     assert out[0] == 0.0 and h[0] == 0.25 and w[0] == 1.25
+
+
+# ---- one scheduled batch: direct prefix + aggregated groups (Sec. 5.2) ----------
+
+def test_grouped_hand_case_from_the_four_worker_example():
+    """Sec. 3.2: g1 and g2 reach the server directly, g3 and g4 are summed at an
+    aggregator and arrive as r = g3 + g4.  With gamma = 1/2, lr = 1, w0 = 0, h0 = 0:
+      g1 = 1:  h = -1        w = -1
+      g2 = 2:  h = -2.5      w = -3.5
+      r = 4 + 8 = 12:  h = -1.25 - 12 = -13.25   w = -16.75"""
+    ups = [arr(1.0), arr(2.0), arr(4.0), arr(8.0)]
+    w, h = arr(0.0), arr(0.0)
+    oracle.apply_grouped(w, h, ups, [0, 1, 2, 3], None, [1, 1, 2], 1.0, 0.5)
+    assert w[0] == -16.75 and h[0] == -13.25
+
+
+def test_grouped_in_exact_arithmetic():
+    """Three arrivals u1, u2, r = (a3 g3 + a4 g4): unrolling Eq. 2 gives
+    h3 = g^3 h0 + g^2 u1 + g u2 + ur and w3 = w0 + h1 + h2 + h3, checked as rationals."""
+    rng = np.random.default_rng(31)
+    n = 16
+    gamma, lr = Fraction(1, 2), Fraction(1, 4)
+    vals = {k: rng.integers(-32, 33, n) for k in ("w0", "h0", "g1", "g2", "g3", "g4")}
+    ups = [vals[k].astype(np.float32) for k in ("g1", "g2", "g3", "g4")]
+    weights = np.array([1.0, 1.0, 0.5, 0.25], np.float32)
+    w, h = vals["w0"].astype(np.float32), vals["h0"].astype(np.float32)
+    oracle.apply_grouped(w, h, ups, [1, 0, 3, 2], weights, [1, 1, 2], float(lr), float(gamma))
+    for i in range(n):
+        u_first = -lr * int(vals["g2"][i])                      # order starts with worker 1
+        u_second = -lr * int(vals["g1"][i])
+        u_r = -lr * (Fraction(1, 4) * int(vals["g4"][i]) + Fraction(1, 2) * int(vals["g3"][i]))
+        h1 = gamma * int(vals["h0"][i]) + u_first
+        h2 = gamma * h1 + u_second
+        h3 = gamma * h2 + u_r
+        assert Fraction(float(h[i])) == h3
+        assert Fraction(float(w[i])) == int(vals["w0"][i]) + h1 + h2 + h3
+
+
+@pytest.mark.parametrize("cfg_name", ["cfg2", "cfg4"])
+def test_grouped_reduces_to_the_other_calls(cfg_name):
+    cfg = W.scaled(W.CONFIGS[cfg_name], n=2053)
+    d = W.dense_inputs(cfg, "cpu", momentum_init="random")
+    ups = [W.to_host(u) for u in d["updates"]]
+    M = len(d["order"])
+
+    def fresh():
+        return W.to_host(d["model"]), W.to_host(d["momentum"])
+
+    # all groups of length 1, no weights  ==  apply_ordered
+    w1, h1 = fresh()
+    oracle.apply_grouped(w1, h1, ups, d["order"], None, [1] * M, d["lr"], d["mu"])
+    w2, h2 = fresh()
+    oracle.apply_ordered(w2, h2, ups, d["order"], d["lr"], d["mu"])
+    assert np.array_equal(bits(w1), bits(w2)) and np.array_equal(bits(h1), bits(h2))
+    # one group  ==  aggregate_apply
+    w1, h1 = fresh()
+    oracle.apply_grouped(w1, h1, ups, d["order"], d["weights"], [M], d["lr"], d["mu"])
+    w2, h2 = fresh()
+    oracle.aggregate_apply(w2, h2, ups, d["order"], d["weights"], d["lr"], d["mu"])
+    assert np.array_equal(bits(w1), bits(w2)) and np.array_equal(bits(h1), bits(h2))
+    # a direct prefix and two aggregated groups == aggregates computed apart, then applied
+    lens = [1, 1, 3, M - 5]
+    w1, h1 = fresh()
+    oracle.apply_grouped(w1, h1, ups, d["order"], d["weights"], lens, d["lr"], d["mu"])
+    arrivals, first = [], 0
+    for ln in lens:
+        arrivals.append(oracle.aggregate(ups, d["order"][first:first + ln], d["weights"]))
+        first += ln
+    w2, h2 = fresh()
+    oracle.apply_ordered(w2, h2, arrivals, list(range(len(lens))), d["lr"], d["mu"])
+    assert np.array_equal(bits(w1), bits(w2)) and np.array_equal(bits(h1), bits(h2))
+
+
+def test_grouped_rejects_bad_lengths():
+    ups = [arr(1.0), arr(2.0)]
+    for lens in ([1], [1, 2], [0, 2], [2, 0]):
+        with pytest.raises(ValueError):
+            oracle.apply_grouped(arr(0.0), arr(0.0), ups, [0, 1], None, lens, 1.0, 0.5)
