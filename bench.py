@@ -63,8 +63,13 @@ class DenseJob:
         self.out = None
         if self.call == "aggregate":
             self.out = torch.empty(cfg.n, device="cuda:0")
-        state = {"aggregate": 4, "apply_ordered": 16 if d["momentum"] is not None else 8,
-                 "aggregate_apply": 16 if d["momentum"] is not None else 8}[self.call]
+        with_h = 16 if d["momentum"] is not None else 8
+        state = {"aggregate": 4, "apply_ordered": with_h, "aggregate_apply": with_h,
+                 "apply_grouped": with_h}[self.call]
+        # a scheduled batch: a quarter of the updates forwarded directly, the rest
+        # in three aggregated groups (Sec. 5.2 of the paper)
+        M = len(d["order"])
+        self.group_len = [1] * (M // 4) + [(M - M // 4) // 3] * 2 + [M - M // 4 - 2 * ((M - M // 4) // 3)]
         self.bytes = (cfg.in_bytes * len(d["order"]) + state) * cfg.n
         self.units = len(d["order"]) * cfg.n          # update elements consumed per step
         self.kernel = "dense_kernel"
@@ -75,6 +80,9 @@ class DenseJob:
             m.mlf_aggregate(d["updates"], d["order"], d["weights"], self.out)
         elif self.call == "apply_ordered":
             m.mlf_apply_ordered(d["model"], d["momentum"], d["updates"], d["order"], d["lr"], d["mu"])
+        elif self.call == "apply_grouped":
+            m.mlf_apply_grouped(d["model"], d["momentum"], d["updates"], d["order"], d["weights"],
+                                self.group_len, d["lr"], d["mu"])
         else:
             m.mlf_aggregate_apply(d["model"], d["momentum"], None, d["updates"], d["order"],
                                   d["weights"], d["lr"], d["mu"])
@@ -251,7 +259,7 @@ def main():
         torch.cuda.empty_cache()
         rows = {}
         plan = [("cfg1", None), ("cfg2", "aggregate"), ("cfg2", None), ("cfg3", None),
-                ("cfg4", None), ("cfg5", None)]
+                ("cfg3", "apply_grouped"), ("cfg4", None), ("cfg5", None)]
         for name, call in plan:
             j = make(name, call)
             _, ev = time_steps(torch, j, 20, 3)

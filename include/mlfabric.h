@@ -123,6 +123,34 @@ mlf_status mlf_aggregate_apply(float *model, float *momentum, float *out_or_null
                                mlf_stream stream);
 
 /*
+ * One scheduled batch as it reaches the server (Sec. 5.2 "Aggregation" and
+ * Alg. 3: the ordered updates are cut into consecutive groups; the first group
+ * is forwarded to the server directly, every later group is summed at an
+ * aggregator and arrives as one update; the order is kept throughout).  Group j
+ * covers the next group_len[j] entries of `order`.  For each group, in sequence,
+ *
+ *   a = sum over the group of weights[order[t]] * U_{order[t]}   (as mlf_aggregate)
+ *   p = mu * h ;  q = lr * a ;  h = p - q ;  w = w + h            (as mlf_apply_ordered)
+ *
+ * all in ONE pass over model and momentum and with every update read once; no
+ * aggregate is written to memory.  A directly forwarded update is a group of
+ * length 1.  Bit-identical to calling mlf_aggregate per group and then
+ * mlf_apply_ordered over the aggregates.  All groups of length 1 without weights
+ * is mlf_apply_ordered; a single group is mlf_aggregate_apply.
+ *
+ *   group_len  host  n_groups positive lengths that add up to n_order
+ *   others     as for mlf_aggregate / mlf_apply_ordered
+ *
+ * MLF_EINVAL additionally for a length < 1 or lengths that do not add up to
+ * n_order.  n_order == 0 (with n_groups == 0) or n == 0 does nothing.
+ */
+mlf_status mlf_apply_grouped(float *model, float *momentum,
+                             const void *const *update_ptrs, int K, int64_t n,
+                             mlf_dtype dtype, const int32_t *order, int n_order,
+                             const float *weights, const int32_t *group_len,
+                             int n_groups, float lr, float mu, mlf_stream stream);
+
+/*
  * LDA count deltas (Sec. 6 "Datasets and ML models": each LDA worker computes a
  * numerical update to the word-topic matrix).  For every triple
  * (word, topic, delta) of every buffer:

@@ -53,6 +53,10 @@ def raw():
                                         _c.c_int64, _c.c_int, i32p, _c.c_int, f32p,
                                         _c.c_float, _c.c_float, _c.c_void_p]
     lib.mlf_aggregate_apply.restype = _c.c_int
+    lib.mlf_apply_grouped.argtypes = [_c.c_void_p, _c.c_void_p, vpp, _c.c_int, _c.c_int64,
+                                      _c.c_int, i32p, _c.c_int, f32p, i32p, _c.c_int,
+                                      _c.c_float, _c.c_float, _c.c_void_p]
+    lib.mlf_apply_grouped.restype = _c.c_int
     lib.mlf_sparse_scatter_add.argtypes = [_c.c_void_p, _c.c_void_p, _c.c_int32, _c.c_int32,
                                            vpp, _c.POINTER(_c.c_int64), _c.c_int,
                                            _c.c_void_p, _c.c_size_t, _c.c_void_p,
@@ -161,6 +165,21 @@ def mlf_aggregate_apply(model, momentum, out, updates, order, weights, lr, mu, n
     tab, K, kind, o, op, w, wp = _dense_tables(updates, order, weights, n)
     st = raw().mlf_aggregate_apply(_ptr(model), _ptr(momentum), _ptr(out), tab, K, n, kind,
                                    op, len(o), wp, float(lr), float(mu), _stream(stream))
+    return _done(st, check)
+
+
+def mlf_apply_grouped(model, momentum, updates, order, weights, group_len, lr, mu, n=None,
+                      stream=None, check=True):
+    """Consecutive groups of the order, each summed and applied as one server
+    step, in one pass (a directly forwarded update is a group of length 1)."""
+    n = model.numel() if n is None else int(n)
+    _state(model, n, "model")
+    _state(momentum, n, "momentum")
+    tab, K, kind, o, op, w, wp = _dense_tables(updates, order, weights, n)
+    g = np.ascontiguousarray(np.asarray(group_len, dtype=np.int32).reshape(-1))
+    gp = g.ctypes.data_as(_c.POINTER(_c.c_int32))
+    st = raw().mlf_apply_grouped(_ptr(model), _ptr(momentum), tab, K, n, kind, op, len(o), wp,
+                                 gp, len(g), float(lr), float(mu), _stream(stream))
     return _done(st, check)
 
 

@@ -44,7 +44,9 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-enum Op { kAggregate = 0, kAggregateApply = 1, kApplyOrdered = 2 };
+static_assert(MLF_MAX_K <= 64, "group boundaries are one bit per sequence position");
+
+enum Op { kAggregate = 0, kAggregateApply = 1, kApplyOrdered = 2, kApplyGrouped = 3 };
 
 // Model + momentum up to this size are left to the caches between calls.
 constexpr long long kInfinityCacheBytes = 256ll << 20;
@@ -60,6 +62,7 @@ struct DenseArgs {
     float *model;
     float *momentum;
     float *out;
+    unsigned long long group_end;   // kApplyGrouped: bit t set = position t closes a group
     long long n;            // elements
     long long n_vec;        // leading elements on the 128-bit path (0 if unaligned)
     unsigned tiles_vec;     // workgroups [0, tiles_vec) each own one 128-bit tile
@@ -231,12 +234,21 @@ struct Tile {
         for (int c = 0; c < C; ++c) {
             const float wt = a.wt[t0 + c];
             const bool first = (c == 0) && (t0 == 0);
+            // Grouped apply: a position opens a group when its predecessor closed
+            // one; uniform over the wavefront (scalar tests of the bit mask).
+            const int t = t0 + c;
+            const bool closes = OP == kApplyGrouped && ((a.group_end >> t) & 1ull) != 0;
+            const bool opens = OP == kApplyGrouped && (t == 0 || ((a.group_end >> (t - 1)) & 1ull) != 0);
 #pragma unroll
             for (int v = 0; v < VPT; ++v) {
 #pragma unroll
                 for (int j = 0; j < W; ++j) {
                     if constexpr (OP == kApplyOrdered) {
                         server_step<HAS_H>(w[v][j], h[v][j], x[c][v][j], a.lr, a.mu);
+                    } else if constexpr (OP == kApplyGrouped) {
+                        const float term = wt * x[c][v][j];
+                        acc[v][j] = opens ? term : acc[v][j] + term;
+                        if (closes) server_step<HAS_H>(w[v][j], h[v][j], acc[v][j], a.lr, a.mu);
                     } else {
                         const float term = wt * x[c][v][j];
                         // The first term starts the sum; later ones are added.
@@ -461,6 +473,7 @@ extern "C" mlf_status mlf_aggregate(const void *const *update_ptrs, int K, int64
     mlf_status st = prepare(a, update_ptrs, K, n, dtype, order, n_order, weights, written, 1);
     if (st != MLF_OK) return st;
     if (n == 0) return MLF_OK;
+    a.group_end = 0;
     a.model = nullptr;
     a.momentum = nullptr;
     a.out = out;
@@ -481,6 +494,7 @@ extern "C" mlf_status mlf_apply_ordered(float *model, float *momentum,
     mlf_status st = prepare(a, update_ptrs, K, n, dtype, order, n_order, nullptr, written, 2);
     if (st != MLF_OK) return st;
     if (n == 0 || n_order == 0) return MLF_OK;
+    a.group_end = 0;
     a.model = model;
     a.momentum = momentum;
     a.out = nullptr;
@@ -502,6 +516,7 @@ extern "C" mlf_status mlf_aggregate_apply(float *model, float *momentum, float *
     mlf_status st = prepare(a, update_ptrs, K, n, dtype, order, n_order, weights, written, 3);
     if (st != MLF_OK) return st;
     if (n == 0) return MLF_OK;
+    a.group_end = 0;
     a.model = model;
     a.momentum = momentum;
     a.out = out_or_null;
@@ -509,6 +524,35 @@ extern "C" mlf_status mlf_aggregate_apply(float *model, float *momentum, float *
     a.mu = mu;
     hipStream_t s = static_cast<hipStream_t>(stream);
     return dispatch<kAggregateApply>(a, dtype, s);
+}
+
+extern "C" mlf_status mlf_apply_grouped(float *model, float *momentum,
+                                        const void *const *update_ptrs, int K, int64_t n,
+                                        mlf_dtype dtype, const int32_t *order, int n_order,
+                                        const float *weights, const int32_t *group_len,
+                                        int n_groups, float lr, float mu, mlf_stream stream)
+{
+    if (model == nullptr || n_groups < 0 || (n_groups > 0 && group_len == nullptr)) return MLF_EINVAL;
+    DenseArgs a;
+    float *written[2] = {model, momentum};
+    mlf_status st = prepare(a, update_ptrs, K, n, dtype, order, n_order, weights, written, 2);
+    if (st != MLF_OK) return st;
+    // The groups tile the committed sequence: positive lengths that add up to it.
+    long long covered = 0;
+    a.group_end = 0;
+    for (int j = 0; j < n_groups; ++j) {
+        if (group_len[j] < 1 || covered + group_len[j] > n_order) return MLF_EINVAL;
+        covered += group_len[j];
+        a.group_end |= 1ull << (covered - 1);
+    }
+    if (covered != n_order) return MLF_EINVAL;
+    if (n == 0 || n_order == 0) return MLF_OK;
+    a.model = model;
+    a.momentum = momentum;
+    a.out = nullptr;
+    a.lr = lr;
+    a.mu = mu;
+    return dispatch<kApplyGrouped>(a, dtype, static_cast<hipStream_t>(stream));
 }
 
 extern "C" const char *mlf_status_string(mlf_status status)

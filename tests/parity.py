@@ -48,6 +48,11 @@ def run_dense(call, d, want_out=False, threads=ORACLE_THREADS):
     if call == "apply_ordered":
         mlf.mlf_apply_ordered(model, momentum, d["updates"], order, d["lr"], d["mu"])
         oracle.apply_ordered(w_h, h_h, ups_h, order, d["lr"], d["mu"], threads=threads)
+    elif call == "apply_grouped":
+        mlf.mlf_apply_grouped(model, momentum, d["updates"], order, weights, d["group_len"],
+                              d["lr"], d["mu"])
+        oracle.apply_grouped(w_h, h_h, ups_h, order, weights, d["group_len"], d["lr"], d["mu"],
+                             threads=threads)
     else:
         out = torch.full((n,), 7.0, device="cuda") if want_out else None
         mlf.mlf_aggregate_apply(model, momentum, out, d["updates"], order, weights,

@@ -22,7 +22,7 @@ def declared_functions():
 
 def test_every_declared_symbol_is_exported():
     names = declared_functions()
-    assert {"mlf_aggregate", "mlf_apply_ordered", "mlf_aggregate_apply",
+    assert {"mlf_aggregate", "mlf_apply_ordered", "mlf_aggregate_apply", "mlf_apply_grouped",
             "mlf_sparse_scatter_add", "mlf_sparse_workspace_bytes",
             "mlf_status_string"} <= set(names)
     lib = ctypes.CDLL(mlf.library_path())
@@ -87,6 +87,26 @@ def test_apply_argument_checks():
                                    None) == B.MLF_EINVAL
     assert lib.mlf_aggregate_apply(None, h, None, tab(u0), 1, 8, 0, o, m, None, 0.1, 0.9,
                                    None) == B.MLF_EINVAL
+
+
+def test_grouped_argument_checks():
+    lib = B.raw()
+    u0, u1, w, h = FAKE, FAKE + 0x100000, FAKE + 0x200000, FAKE + 0x300000
+    o, m = order(0, 1)
+
+    def call(lens, n=8):
+        g = (ctypes.c_int32 * max(len(lens), 1))(*lens)
+        return lib.mlf_apply_grouped(w, h, tab(u0, u1), 2, n, 0, o, m, None, g, len(lens),
+                                     0.1, 0.9, None)
+
+    assert call([1, 1], n=0) == B.MLF_OK
+    assert call([1]) == B.MLF_EINVAL             # does not cover the order
+    assert call([1, 2]) == B.MLF_EINVAL          # overshoots
+    assert call([2, 0]) == B.MLF_EINVAL          # empty group
+    assert call([0, 2]) == B.MLF_EINVAL
+    assert call([]) == B.MLF_EINVAL
+    assert lib.mlf_apply_grouped(None, h, tab(u0, u1), 2, 8, 0, o, m, None,
+                                 (ctypes.c_int32 * 1)(2), 1, 0.1, 0.9, None) == B.MLF_EINVAL
 
 
 def test_sparse_argument_checks():

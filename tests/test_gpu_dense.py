@@ -210,3 +210,70 @@ def test_launch_on_a_side_stream():
     mlf.mlf_aggregate(d["updates"], d["order"], d["weights"], out_b, stream=s)
     s.synchronize()
     assert torch.equal(out_a.view(torch.int32), out_b.view(torch.int32))
+
+
+# ---- one scheduled batch: direct prefix + aggregated groups ----------------------
+
+def split_into_groups(M, seed, n_direct=None):
+    """A direct prefix of singleton groups followed by random aggregated groups."""
+    rng = np.random.default_rng(seed)
+    n_direct = int(rng.integers(0, M + 1)) if n_direct is None else n_direct
+    lens, left = [1] * n_direct, M - n_direct
+    while left > 0:
+        ln = int(rng.integers(1, left + 1))
+        lens.append(ln)
+        left -= ln
+    return lens
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("K", [1, 2, 5, 16, 17, 33, 64])
+def test_grouped_apply(dtype, K):
+    for n in (1, 9, 257, 6151, 70_001):
+        cfg = recipe("cfg2", n=n, K=K, dtype=dtype)
+        d = W.dense_inputs(cfg, "cuda", momentum_init="random", n_dropped=K // 5)
+        d["weights"] = np.random.default_rng(K).uniform(0.1, 2.0, K).astype(np.float32)
+        d["group_len"] = split_into_groups(len(d["order"]), seed=K * 1000 + n)
+        run_dense("apply_grouped", d)
+
+
+def test_grouped_apply_without_momentum_or_weights_and_misaligned():
+    cfg = recipe("cfg1", n=40_004, K=7)
+    d = W.dense_inputs(cfg, "cuda")
+    d["weights"] = None
+    d["group_len"] = [1, 1, 2, 3]
+    run_dense("apply_grouped", d)
+    d["model"] = d["model"][1:]
+    d["updates"] = [u[:cfg.n - 1] for u in d["updates"]]
+    run_dense("apply_grouped", d)
+
+
+def test_grouped_apply_reduces_to_the_other_calls_on_the_gpu():
+    cfg = recipe("cfg2", n=123_457)
+    d = W.dense_inputs(cfg, "cuda", momentum_init="random")
+    M = len(d["order"])
+    w1, h1 = d["model"].clone(), d["momentum"].clone()
+    mlf.mlf_apply_grouped(w1, h1, d["updates"], d["order"], None, [1] * M, d["lr"], d["mu"])
+    w2, h2 = d["model"].clone(), d["momentum"].clone()
+    mlf.mlf_apply_ordered(w2, h2, d["updates"], d["order"], d["lr"], d["mu"])
+    assert torch.equal(w1.view(torch.int32), w2.view(torch.int32))
+    assert torch.equal(h1.view(torch.int32), h2.view(torch.int32))
+    w1, h1 = d["model"].clone(), d["momentum"].clone()
+    mlf.mlf_apply_grouped(w1, h1, d["updates"], d["order"], d["weights"], [M], d["lr"], d["mu"])
+    w2, h2 = d["model"].clone(), d["momentum"].clone()
+    mlf.mlf_aggregate_apply(w2, h2, None, d["updates"], d["order"], d["weights"], d["lr"], d["mu"])
+    assert torch.equal(w1.view(torch.int32), w2.view(torch.int32))
+    assert torch.equal(h1.view(torch.int32), h2.view(torch.int32))
+
+
+def test_grouped_apply_full_size_alexnet_batch():
+    """cfg3's 32 updates as a scheduled batch: 8 forwarded directly, then three
+    aggregated groups of 8 (state above the Infinity Cache: streamed)."""
+    cfg = W.CONFIGS["cfg3"]
+    d = W.dense_inputs(cfg, "cuda")
+    d["weights"] = np.full(cfg.K, 0.125, np.float32)
+    d["weights"][d["order"][:8]] = 1.0
+    d["group_len"] = [1] * 8 + [8, 8, 8]
+    run_dense("apply_grouped", d)
+    del d
+    torch.cuda.empty_cache()
