@@ -64,6 +64,10 @@ def _load():
         f.argtypes = [c.c_void_p, c.c_void_p, pp, c.c_int, c.c_int64, i32p, c.c_int,
                       f32p, i32p, c.c_int, c.c_float, c.c_float]
         f.restype = None
+    lib.orc_sum_sq_f32.argtypes = [c.c_void_p, c.c_int64]
+    lib.orc_sum_sq_f32.restype = c.c_double
+    lib.orc_sum_sq_diff_f32.argtypes = [c.c_void_p, c.c_void_p, c.c_int64]
+    lib.orc_sum_sq_diff_f32.restype = c.c_double
     lib.orc_scatter_add.argtypes = [c.c_void_p, c.c_void_p, c.c_int32,
                                     c.c_int32, pp, c.POINTER(c.c_int64),
                                     c.c_int, c.c_int32, c.c_int32, c.c_int32,
@@ -238,6 +242,30 @@ def apply_grouped(model, momentum, updates, order, weights, group_len, lr, mu, t
                           gp, len(g), float(lr), float(mu))
 
     _run([job(lo, hi) for lo, hi in _slices(n, threads)], threads)
+
+
+def sum_sq(x, threads=1):
+    """||x||_2^2 of a float32 vector: correctly rounded to binary64 with one
+    thread; with several, each slice's exact sum is rounded before the slices are
+    combined (exactly), so the result is within a few units in the last place."""
+    import math
+    lib = _load()
+    _f32_inplace(x, "x", x.shape[0])
+    jobs = [(lambda lo=lo, hi=hi: lib.orc_sum_sq_f32(x.ctypes.data + 4 * lo, hi - lo))
+            for lo, hi in _slices(x.shape[0], threads)]
+    return math.fsum(_run(jobs, threads))
+
+
+def sum_sq_diff(a, b, threads=1):
+    """||a - b||_2^2 of two float32 vectors, the differences taken exactly."""
+    import math
+    lib = _load()
+    _f32_inplace(a, "a", a.shape[0])
+    _f32_inplace(b, "b", a.shape[0])
+    jobs = [(lambda lo=lo, hi=hi: lib.orc_sum_sq_diff_f32(a.ctypes.data + 4 * lo,
+                                                          b.ctypes.data + 4 * lo, hi - lo))
+            for lo, hi in _slices(a.shape[0], threads)]
+    return math.fsum(_run(jobs, threads))
 
 
 def scatter_add(counts, totals, V, T, triples, threads=1):

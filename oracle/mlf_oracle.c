@@ -37,6 +37,9 @@
  *                          directly forwarded prefix followed by groups that
  *                          were summed at aggregators; each arrival is one step
  *                          of Eq. 2.
+ *  - orc_sum_sq_*          Table 1 (push carries update_norm) and Sec. 5.3
+ *                          (divergence bound from ||h||, ||u_i||; exact
+ *                          divergence ||w_s - w_r||): squared 2-norms.
  *  - orc_scatter_add       Sec. 6 "Datasets and ML models": an LDA worker's
  *                          update is a numerical update to the word-topic count
  *                          matrix; here it arrives as (word, topic, delta)
@@ -282,6 +285,33 @@ void orc_apply_grouped_bf16(float *model, float *momentum,
             momentum[i] = h;
         }
     }
+}
+
+/* ------------------------------------------------------------------------ */
+/* Squared Euclidean norms (Table 1: a push carries update_norm; Sec. 5.3: the */
+/* divergence bound is built from ||h|| and ||u_i||, and the exact divergence   */
+/* is ||w_s - w_r||_2).  Squares of binary32 values and their differences are  */
+/* exact in binary128, and the running sum is kept in binary128, so the value  */
+/* returned is the true sum rounded (up to 2^-100 or so) to binary64.          */
+/* ------------------------------------------------------------------------ */
+double orc_sum_sq_f32(const float *x, int64_t n)
+{
+    __float128 acc = 0;
+    for (int64_t i = 0; i < n; ++i) {
+        __float128 v = x[i];
+        acc += v * v;
+    }
+    return (double)acc;
+}
+
+double orc_sum_sq_diff_f32(const float *a, const float *b, int64_t n)
+{
+    __float128 acc = 0;
+    for (int64_t i = 0; i < n; ++i) {
+        __float128 d = (__float128)a[i] - (__float128)b[i];
+        acc += d * d;
+    }
+    return (double)acc;
 }
 
 /* ------------------------------------------------------------------------ */
