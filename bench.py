@@ -65,7 +65,11 @@ class DenseJob:
             self.out = torch.empty(cfg.n, device="cuda:0")
         with_h = 16 if d["momentum"] is not None else 8
         state = {"aggregate": 4, "apply_ordered": with_h, "aggregate_apply": with_h,
-                 "apply_grouped": with_h}[self.call]
+                 "apply_grouped": with_h, "apply_grouped_norms": with_h}[self.call]
+        if self.call == "apply_grouped_norms":
+            self.norms = torch.zeros(2, dtype=torch.float64, device="cuda:0")
+            self.norm_ws = torch.empty(mlf.mlf_norms_workspace_bytes(cfg.n), dtype=torch.uint8,
+                                       device="cuda:0")
         # a scheduled batch: a quarter of the updates forwarded directly, the rest
         # in three aggregated groups (Sec. 5.2 of the paper)
         M = len(d["order"])
@@ -83,6 +87,10 @@ class DenseJob:
         elif self.call == "apply_grouped":
             m.mlf_apply_grouped(d["model"], d["momentum"], d["updates"], d["order"], d["weights"],
                                 self.group_len, d["lr"], d["mu"])
+        elif self.call == "apply_grouped_norms":
+            m.mlf_apply_grouped_norms(d["model"], d["momentum"], d["updates"], d["order"],
+                                      d["weights"], self.group_len, d["lr"], d["mu"], self.norms,
+                                      self.norm_ws)
         else:
             m.mlf_aggregate_apply(d["model"], d["momentum"], None, d["updates"], d["order"],
                                   d["weights"], d["lr"], d["mu"])
@@ -259,7 +267,9 @@ def main():
         torch.cuda.empty_cache()
         rows = {}
         plan = [("cfg1", None), ("cfg2", "aggregate"), ("cfg2", None), ("cfg3", None),
-                ("cfg3", "apply_grouped"), ("cfg4", None), ("cfg5", None)]
+                ("cfg3", "apply_grouped"), ("cfg2", "apply_grouped"),
+                ("cfg2", "apply_grouped_norms"), ("cfg3", "apply_grouped_norms"), ("cfg4", None),
+                ("cfg5", None)]
         for name, call in plan:
             j = make(name, call)
             _, ev = time_steps(torch, j, 20, 3)

@@ -151,6 +151,48 @@ mlf_status mlf_apply_grouped(float *model, float *momentum,
                              int n_groups, float lr, float mu, mlf_stream stream);
 
 /*
+ * Norms for the scheduler, fused into the passes above at no extra HBM traffic.
+ * A push carries the update's norm (Table 1, push(server, update, update_norm)),
+ * and the scheduler bounds the server-replica divergence from ||h|| and the
+ * ||u_i|| alone because the exact divergence ||w_s - w_r||_2 is costly to
+ * compute (Sec. 5.3); here both come out of the pass that is made anyway.
+ *
+ * mlf_aggregate_norm: mlf_aggregate, and norm_sq[0] = sum_i out[i]^2 -- the
+ * squared norm of the aggregate an aggregator forwards.
+ *
+ * mlf_apply_grouped_norms: mlf_apply_grouped, and
+ *   norms_sq[0] = sum_i h[i]^2 of the history after the call (0 without momentum)
+ *   norms_sq[1] = sum_i (w_after[i] - w_before[i])^2: the exact squared divergence
+ *                 between the server after this batch and a replica that has not
+ *                 applied it yet.
+ * With n_order == 0 the model is left as it is and the norms describe it.
+ *
+ * The sums are taken in binary64 (squares of binary32 values are exact there; a
+ * difference w_after - w_before is rounded once to binary64), in an order fixed
+ * by n and the data type alone, so they are reproducible bit for bit; they agree
+ * with the exactly rounded sums to about 1e-14 relative.
+ *
+ *   norm_sq / norms_sq  device, 1 / 2 doubles, 8-byte aligned; written
+ *   workspace           device scratch of mlf_norms_workspace_bytes(n) bytes,
+ *                       8-byte aligned (MLF_EINVAL if NULL or too small)
+ */
+size_t mlf_norms_workspace_bytes(int64_t n);
+
+mlf_status mlf_aggregate_norm(const void *const *update_ptrs, int K, int64_t n,
+                              mlf_dtype dtype, const int32_t *order, int n_order,
+                              const float *weights, float *out, double *norm_sq,
+                              void *workspace, size_t workspace_bytes,
+                              mlf_stream stream);
+
+mlf_status mlf_apply_grouped_norms(float *model, float *momentum,
+                                   const void *const *update_ptrs, int K, int64_t n,
+                                   mlf_dtype dtype, const int32_t *order, int n_order,
+                                   const float *weights, const int32_t *group_len,
+                                   int n_groups, float lr, float mu, double *norms_sq,
+                                   void *workspace, size_t workspace_bytes,
+                                   mlf_stream stream);
+
+/*
  * LDA count deltas (Sec. 6 "Datasets and ML models": each LDA worker computes a
  * numerical update to the word-topic matrix).  For every triple
  * (word, topic, delta) of every buffer:

@@ -11,7 +11,10 @@ from .binding import (  # noqa: F401
     library_path,
     mlf_aggregate,
     mlf_aggregate_apply,
+    mlf_aggregate_norm,
     mlf_apply_grouped,
+    mlf_apply_grouped_norms,
+    mlf_norms_workspace_bytes,
     mlf_apply_ordered,
     mlf_sparse_scatter_add,
     mlf_sparse_workspace_bytes,

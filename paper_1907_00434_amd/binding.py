@@ -57,6 +57,17 @@ def raw():
                                       _c.c_int, i32p, _c.c_int, f32p, i32p, _c.c_int,
                                       _c.c_float, _c.c_float, _c.c_void_p]
     lib.mlf_apply_grouped.restype = _c.c_int
+    lib.mlf_norms_workspace_bytes.argtypes = [_c.c_int64]
+    lib.mlf_norms_workspace_bytes.restype = _c.c_size_t
+    lib.mlf_aggregate_norm.argtypes = [vpp, _c.c_int, _c.c_int64, _c.c_int, i32p, _c.c_int,
+                                       f32p, _c.c_void_p, _c.c_void_p, _c.c_void_p,
+                                       _c.c_size_t, _c.c_void_p]
+    lib.mlf_aggregate_norm.restype = _c.c_int
+    lib.mlf_apply_grouped_norms.argtypes = [_c.c_void_p, _c.c_void_p, vpp, _c.c_int, _c.c_int64,
+                                            _c.c_int, i32p, _c.c_int, f32p, i32p, _c.c_int,
+                                            _c.c_float, _c.c_float, _c.c_void_p, _c.c_void_p,
+                                            _c.c_size_t, _c.c_void_p]
+    lib.mlf_apply_grouped_norms.restype = _c.c_int
     lib.mlf_sparse_scatter_add.argtypes = [_c.c_void_p, _c.c_void_p, _c.c_int32, _c.c_int32,
                                            vpp, _c.POINTER(_c.c_int64), _c.c_int,
                                            _c.c_void_p, _c.c_size_t, _c.c_void_p,
@@ -180,6 +191,44 @@ def mlf_apply_grouped(model, momentum, updates, order, weights, group_len, lr, m
     gp = g.ctypes.data_as(_c.POINTER(_c.c_int32))
     st = raw().mlf_apply_grouped(_ptr(model), _ptr(momentum), tab, K, n, kind, op, len(o), wp,
                                  gp, len(g), float(lr), float(mu), _stream(stream))
+    return _done(st, check)
+
+
+def mlf_norms_workspace_bytes(n) -> int:
+    return int(raw().mlf_norms_workspace_bytes(int(n)))
+
+
+def _nbytes(t):
+    return 0 if t is None else t.numel() * t.element_size()
+
+
+def mlf_aggregate_norm(updates, order, weights, out, norm_sq, workspace, n=None, stream=None,
+                       check=True):
+    """mlf_aggregate, plus norm_sq[0] = sum of out^2 (float64 device tensor)."""
+    n = out.numel() if n is None else int(n)
+    _state(out, n, "out")
+    if norm_sq.dtype != torch.float64 or norm_sq.numel() < 1:
+        raise ValueError("norm_sq must be a float64 device tensor")
+    tab, K, kind, o, op, w, wp = _dense_tables(updates, order, weights, n)
+    st = raw().mlf_aggregate_norm(tab, K, n, kind, op, len(o), wp, _ptr(out), _ptr(norm_sq),
+                                  _ptr(workspace), _nbytes(workspace), _stream(stream))
+    return _done(st, check)
+
+
+def mlf_apply_grouped_norms(model, momentum, updates, order, weights, group_len, lr, mu,
+                            norms_sq, workspace, n=None, stream=None, check=True):
+    """mlf_apply_grouped, plus norms_sq = [sum h_after^2, sum (w_after - w_before)^2]."""
+    n = model.numel() if n is None else int(n)
+    _state(model, n, "model")
+    _state(momentum, n, "momentum")
+    if norms_sq.dtype != torch.float64 or norms_sq.numel() < 2:
+        raise ValueError("norms_sq must be a float64 device tensor of 2 elements")
+    tab, K, kind, o, op, w, wp = _dense_tables(updates, order, weights, n)
+    g = np.ascontiguousarray(np.asarray(group_len, dtype=np.int32).reshape(-1))
+    gp = g.ctypes.data_as(_c.POINTER(_c.c_int32))
+    st = raw().mlf_apply_grouped_norms(_ptr(model), _ptr(momentum), tab, K, n, kind, op, len(o),
+                                       wp, gp, len(g), float(lr), float(mu), _ptr(norms_sq),
+                                       _ptr(workspace), _nbytes(workspace), _stream(stream))
     return _done(st, check)
 
 

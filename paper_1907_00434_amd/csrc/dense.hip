@@ -29,6 +29,9 @@
 #ifndef MLF_SHAPE_BF16V4      // bfloat16, 4 elements per lane and group
 #define MLF_SHAPE_BF16V4 64, 2, 8
 #endif
+#ifndef MLF_SHAPE_NORMS       // variants that also reduce norms (one wavefront per workgroup)
+#define MLF_SHAPE_NORMS 64, 2, 8
+#endif
 #ifndef MLF_SHAPE_BF16V8      // bfloat16, 8 elements per lane and group
 #define MLF_SHAPE_BF16V8 256, 1, 8
 #endif
@@ -63,6 +66,7 @@ struct DenseArgs {
     float *momentum;
     float *out;
     unsigned long long group_end;   // kApplyGrouped: bit t set = position t closes a group
+    double *partials;       // norms variants: two partial sums per workgroup
     long long n;            // elements
     long long n_vec;        // leading elements on the 128-bit path (0 if unaligned)
     unsigned tiles_vec;     // workgroups [0, tiles_vec) each own one 128-bit tile
@@ -189,8 +193,8 @@ __device__ __forceinline__ void server_step(float &w, float &h, float g, float l
 //   e0       first element of the region the groups are counted in
 //   g0       this lane's first group in that region
 //   n_groups groups in the region
-template <typename IN, int W, int OP, bool HAS_H, int STREAM, int THREADS, int VPT, int CH,
-          bool FULL>
+template <typename IN, int W, int OP, bool HAS_H, int STREAM, bool NORMS, int THREADS, int VPT,
+          int CH, bool FULL>
 struct Tile {
     const DenseArgs &a;
     long long e[VPT];       // first element of each group
@@ -198,6 +202,7 @@ struct Tile {
     float acc[VPT][W];      // running sum   (aggregate, aggregate+apply)
     float w[VPT][W];        // model         (apply variants)
     float h[VPT][W];        // history       (apply variants with momentum)
+    float w_old[VPT][W];    // model before the call (norms variants)
 
     __device__ __forceinline__ Tile(const DenseArgs &args, long long e0, long long g0,
                                     long long n_groups)
@@ -272,7 +277,11 @@ struct Tile {
         }
     }
 
-    __device__ __forceinline__ void run()
+    // `sums` (norms variants): this lane's running squared norms in binary64,
+    //   [0] aggregate: out^2          apply variants: history^2 after the call
+    //   [1] apply variants: (model after - model before)^2
+    // A binary32 square is exact in binary64, so only the additions round.
+    __device__ __forceinline__ void run(double (&sums)[2])
     {
 #pragma unroll
         for (int v = 0; v < VPT; ++v) {
@@ -287,6 +296,10 @@ struct Tile {
                     load_state<W, STREAM>(w[v], a.model, e[v]);
                     if constexpr (HAS_H) load_state<W, STREAM>(h[v], a.momentum, e[v]);
                 }
+            }
+            if constexpr (NORMS) {
+#pragma unroll
+                for (int j = 0; j < W; ++j) w_old[v][j] = w[v][j];
             }
         }
 
@@ -310,6 +323,20 @@ struct Tile {
                 store_state<W, STREAM>(a.model, e[v], w[v]);
                 if constexpr (HAS_H) store_state<W, STREAM>(a.momentum, e[v], h[v]);
             }
+            if constexpr (NORMS) {
+#pragma unroll
+                for (int j = 0; j < W; ++j) {
+                    if constexpr (OP == kAggregate) {
+                        const double x = acc[v][j];
+                        sums[0] += x * x;
+                    } else {
+                        const double hh = h[v][j];
+                        const double dw = static_cast<double>(w[v][j]) - static_cast<double>(w_old[v][j]);
+                        sums[0] += hh * hh;
+                        sums[1] += dw * dw;
+                    }
+                }
+            }
         }
     }
 };
@@ -317,26 +344,71 @@ struct Tile {
 // Workgroups [0, tiles_vec) take one tile each of the 128-bit region
 // [0, n_vec); the remaining workgroups stride over the element-wise region
 // [n_vec, n): the ragged tail, or everything when a pointer of the call is not
-// 16-byte aligned.
-template <typename IN, int OP, bool HAS_H, int STREAM, int THREADS, int VPT, int CH>
+// 16-byte aligned.  Norms variants (one wavefront per workgroup) end with a
+// shuffle reduction in a fixed order and one pair of partial sums per workgroup.
+template <typename IN, int OP, bool HAS_H, int STREAM, bool NORMS, int THREADS, int VPT, int CH>
 __global__ __launch_bounds__(THREADS) void dense_kernel(const DenseArgs a)
 {
+    static_assert(!NORMS || THREADS == 64, "norms are reduced within one wavefront");
     constexpr int WV = IN::kVec;
     constexpr long long kTile = static_cast<long long>(THREADS) * VPT;
+    double sums[2] = {0.0, 0.0};
     if (blockIdx.x < a.tiles_vec) {
         const long long groups = a.n_vec / WV;
         const long long base = blockIdx.x * kTile;
         if (base + kTile <= groups) {
-            Tile<IN, WV, OP, HAS_H, STREAM, THREADS, VPT, CH, true>(a, 0, base + threadIdx.x, groups).run();
+            Tile<IN, WV, OP, HAS_H, STREAM, NORMS, THREADS, VPT, CH, true>(a, 0, base + threadIdx.x, groups).run(sums);
         } else {
-            Tile<IN, WV, OP, HAS_H, STREAM, THREADS, VPT, CH, false>(a, 0, base + threadIdx.x, groups).run();
+            Tile<IN, WV, OP, HAS_H, STREAM, NORMS, THREADS, VPT, CH, false>(a, 0, base + threadIdx.x, groups).run(sums);
         }
     } else {
         const long long groups = a.n - a.n_vec;
         const long long stride = static_cast<long long>(gridDim.x - a.tiles_vec) * kTile;
         for (long long base = (blockIdx.x - a.tiles_vec) * kTile; base < groups; base += stride) {
-            Tile<IN, 1, OP, HAS_H, STREAM, THREADS, VPT, CH, false>(a, a.n_vec, base + threadIdx.x, groups).run();
+            Tile<IN, 1, OP, HAS_H, STREAM, NORMS, THREADS, VPT, CH, false>(a, a.n_vec, base + threadIdx.x, groups).run(sums);
         }
+    }
+    if constexpr (NORMS) {
+        double s0 = sums[0], s1 = sums[1];
+        for (int off = 32; off > 0; off >>= 1) {
+            s0 += __shfl_down(s0, off, 64);
+            s1 += __shfl_down(s1, off, 64);
+        }
+        if (threadIdx.x == 0) {
+            a.partials[2 * static_cast<size_t>(blockIdx.x)] = s0;
+            a.partials[2 * static_cast<size_t>(blockIdx.x) + 1] = s1;
+        }
+    }
+}
+
+// Sums the per-workgroup partial sums in a fixed order (lane i takes partials
+// i, i + 1024, ... in turn, then a tree over the lanes), so that the norms of
+// a call are reproducible bit for bit for a given launch shape.
+constexpr int kFinishThreads = 1024;
+
+__global__ __launch_bounds__(kFinishThreads) void norms_finish_kernel(const double *partials,
+                                                                      unsigned n_partials,
+                                                                      double *out, int n_out)
+{
+    __shared__ double tree[2][kFinishThreads];
+    double s0 = 0.0, s1 = 0.0;
+    for (unsigned j = threadIdx.x; j < n_partials; j += kFinishThreads) {
+        s0 += partials[2 * static_cast<size_t>(j)];
+        s1 += partials[2 * static_cast<size_t>(j) + 1];
+    }
+    tree[0][threadIdx.x] = s0;
+    tree[1][threadIdx.x] = s1;
+    __syncthreads();
+    for (int half = kFinishThreads / 2; half > 0; half >>= 1) {
+        if (threadIdx.x < static_cast<unsigned>(half)) {
+            tree[0][threadIdx.x] += tree[0][threadIdx.x + half];
+            tree[1][threadIdx.x] += tree[1][threadIdx.x + half];
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        out[0] = tree[0][0];
+        if (n_out > 1) out[1] = tree[1][0];
     }
 }
 
@@ -356,46 +428,72 @@ Range range_of(const void *p, long long n, size_t elem)
     return Range{lo, lo + static_cast<uintptr_t>(n) * elem};
 }
 
-template <typename IN, int OP, bool HAS_H, int STREAM, int THREADS, int VPT, int CH>
-mlf_status launch_shape(DenseArgs &a, hipStream_t stream)
+// Workgroups a launch of this shape uses (tiles of the 128-bit region plus the
+// workgroups of the element-wise region).
+template <typename IN, int THREADS, int VPT>
+void count_workgroups(const DenseArgs &a, long long &n_vec, long long &tiles_v, long long &tiles_s)
 {
     constexpr long long kTile = static_cast<long long>(THREADS) * VPT;
-    a.n_vec = a.n_vec / IN::kVec * IN::kVec;    // whole groups only
-    const long long tiles_v = (a.n_vec / IN::kVec + kTile - 1) / kTile;
-    long long tiles_s = (a.n - a.n_vec + kTile - 1) / kTile;
+    n_vec = a.n_vec / IN::kVec * IN::kVec;       // whole groups only
+    tiles_v = (n_vec / IN::kVec + kTile - 1) / kTile;
+    tiles_s = (a.n - n_vec + kTile - 1) / kTile;
     if (tiles_s > kMaxScalarGroups) tiles_s = kMaxScalarGroups;
-    if (tiles_v + tiles_s > 0x7fffffffll) return MLF_EUNSUPPORTED;
-    a.tiles_vec = static_cast<unsigned>(tiles_v);
-    dense_kernel<IN, OP, HAS_H, STREAM, THREADS, VPT, CH>
-        <<<dim3(static_cast<unsigned>(tiles_v + tiles_s)), dim3(THREADS), 0, stream>>>(a);
-    return hipGetLastError() == hipSuccess ? MLF_OK : MLF_EHIP;
 }
 
-template <typename IN, int OP, bool HAS_H, int STREAM>
-mlf_status launch(DenseArgs &a, hipStream_t stream)
+template <typename IN, int OP, bool HAS_H, int STREAM, bool NORMS, int THREADS, int VPT, int CH>
+mlf_status launch_shape(DenseArgs &a, hipStream_t stream, double *norms_out,
+                        size_t partials_capacity)
 {
-    if constexpr (sizeof(typename IN::elem) == 4) {
-        return launch_shape<IN, OP, HAS_H, STREAM, MLF_SHAPE_F32>(a, stream);
+    long long n_vec, tiles_v, tiles_s;
+    count_workgroups<IN, THREADS, VPT>(a, n_vec, tiles_v, tiles_s);
+    if (tiles_v + tiles_s > 0x7fffffffll) return MLF_EUNSUPPORTED;
+    if (NORMS && static_cast<size_t>(tiles_v + tiles_s) > partials_capacity) return MLF_EINVAL;
+    a.n_vec = n_vec;
+    a.tiles_vec = static_cast<unsigned>(tiles_v);
+    const unsigned grid = static_cast<unsigned>(tiles_v + tiles_s);
+    if (grid > 0) {
+        dense_kernel<IN, OP, HAS_H, STREAM, NORMS, THREADS, VPT, CH>
+            <<<dim3(grid), dim3(THREADS), 0, stream>>>(a);
+        if (hipGetLastError() != hipSuccess) return MLF_EHIP;
+    }
+    if constexpr (NORMS) {
+        norms_finish_kernel<<<dim3(1), dim3(kFinishThreads), 0, stream>>>(
+            a.partials, grid, norms_out, OP == kAggregate ? 1 : 2);
+        if (hipGetLastError() != hipSuccess) return MLF_EHIP;
+    }
+    return MLF_OK;
+}
+
+template <typename IN, int OP, bool HAS_H, int STREAM, bool NORMS>
+mlf_status launch(DenseArgs &a, hipStream_t stream, double *norms_out, size_t partials_capacity)
+{
+    if constexpr (NORMS) {
+        return launch_shape<IN, OP, HAS_H, STREAM, true, MLF_SHAPE_NORMS>(a, stream, norms_out,
+                                                                          partials_capacity);
+    } else if constexpr (sizeof(typename IN::elem) == 4) {
+        return launch_shape<IN, OP, HAS_H, STREAM, false, MLF_SHAPE_F32>(a, stream, nullptr, 0);
     } else if constexpr (IN::kVec == 4) {
-        return launch_shape<IN, OP, HAS_H, STREAM, MLF_SHAPE_BF16V4>(a, stream);
+        return launch_shape<IN, OP, HAS_H, STREAM, false, MLF_SHAPE_BF16V4>(a, stream, nullptr, 0);
     } else {
-        return launch_shape<IN, OP, HAS_H, STREAM, MLF_SHAPE_BF16V8>(a, stream);
+        return launch_shape<IN, OP, HAS_H, STREAM, false, MLF_SHAPE_BF16V8>(a, stream, nullptr, 0);
     }
 }
 
-template <typename IN, int OP, int STREAM>
-mlf_status dispatch_state(DenseArgs &a, hipStream_t stream)
+template <typename IN, int OP, int STREAM, bool NORMS>
+mlf_status dispatch_state(DenseArgs &a, hipStream_t stream, double *norms_out, size_t capacity)
 {
     if constexpr (OP == kAggregate) {
-        return launch<IN, OP, false, STREAM>(a, stream);
+        return launch<IN, OP, false, STREAM, NORMS>(a, stream, norms_out, capacity);
     } else {
-        return a.momentum != nullptr ? launch<IN, OP, true, STREAM>(a, stream)
-                                     : launch<IN, OP, false, STREAM>(a, stream);
+        return a.momentum != nullptr
+                   ? launch<IN, OP, true, STREAM, NORMS>(a, stream, norms_out, capacity)
+                   : launch<IN, OP, false, STREAM, NORMS>(a, stream, norms_out, capacity);
     }
 }
 
-template <int OP>
-mlf_status dispatch(DenseArgs &a, mlf_dtype dtype, hipStream_t stream)
+template <int OP, bool NORMS = false>
+mlf_status dispatch(DenseArgs &a, mlf_dtype dtype, hipStream_t stream, double *norms_out = nullptr,
+                    size_t capacity = 0)
 {
     // State that is too large to survive in the Infinity Cache until the next
     // call is streamed through; smaller state is left cacheable.
@@ -407,11 +505,11 @@ mlf_status dispatch(DenseArgs &a, mlf_dtype dtype, hipStream_t stream)
     const bool streaming = MLF_STATE_POLICY >= 2 ||
                            (MLF_STATE_POLICY == 0 && footprint > kInfinityCacheBytes);
     if (dtype == MLF_F32) {
-        return streaming ? dispatch_state<F32, OP, kS>(a, stream)
-                         : dispatch_state<F32, OP, 0>(a, stream);
+        return streaming ? dispatch_state<F32, OP, kS, NORMS>(a, stream, norms_out, capacity)
+                         : dispatch_state<F32, OP, 0, NORMS>(a, stream, norms_out, capacity);
     }
-    return streaming ? dispatch_state<BF16V4, OP, kS>(a, stream)
-                     : dispatch_state<BF16V8, OP, 0>(a, stream);
+    return streaming ? dispatch_state<BF16V4, OP, kS, NORMS>(a, stream, norms_out, capacity)
+                     : dispatch_state<BF16V8, OP, 0, NORMS>(a, stream, norms_out, capacity);
 }
 
 // Validates the arguments shared by the three dense calls and fills `a`.
@@ -474,6 +572,7 @@ extern "C" mlf_status mlf_aggregate(const void *const *update_ptrs, int K, int64
     if (st != MLF_OK) return st;
     if (n == 0) return MLF_OK;
     a.group_end = 0;
+    a.partials = nullptr;
     a.model = nullptr;
     a.momentum = nullptr;
     a.out = out;
@@ -495,6 +594,7 @@ extern "C" mlf_status mlf_apply_ordered(float *model, float *momentum,
     if (st != MLF_OK) return st;
     if (n == 0 || n_order == 0) return MLF_OK;
     a.group_end = 0;
+    a.partials = nullptr;
     a.model = model;
     a.momentum = momentum;
     a.out = nullptr;
@@ -517,6 +617,7 @@ extern "C" mlf_status mlf_aggregate_apply(float *model, float *momentum, float *
     if (st != MLF_OK) return st;
     if (n == 0) return MLF_OK;
     a.group_end = 0;
+    a.partials = nullptr;
     a.model = model;
     a.momentum = momentum;
     a.out = out_or_null;
@@ -540,6 +641,7 @@ extern "C" mlf_status mlf_apply_grouped(float *model, float *momentum,
     // The groups tile the committed sequence: positive lengths that add up to it.
     long long covered = 0;
     a.group_end = 0;
+    a.partials = nullptr;
     for (int j = 0; j < n_groups; ++j) {
         if (group_len[j] < 1 || covered + group_len[j] > n_order) return MLF_EINVAL;
         covered += group_len[j];
@@ -553,6 +655,77 @@ extern "C" mlf_status mlf_apply_grouped(float *model, float *momentum,
     a.lr = lr;
     a.mu = mu;
     return dispatch<kApplyGrouped>(a, dtype, static_cast<hipStream_t>(stream));
+}
+
+// Partial sums a norms variant may need: one pair per workgroup of the
+// (64 lanes x 2 groups) shape, for either layout of the elements.
+size_t norms_partials_capacity(long long n)
+{
+    return static_cast<size_t>(n / (64 * 2 * 4)) + 2 + static_cast<size_t>(kMaxScalarGroups);
+}
+
+extern "C" size_t mlf_norms_workspace_bytes(int64_t n)
+{
+    if (n < 0) return 0;
+    return norms_partials_capacity(n) * 2 * sizeof(double);
+}
+
+extern "C" mlf_status mlf_aggregate_norm(const void *const *update_ptrs, int K, int64_t n,
+                                         mlf_dtype dtype, const int32_t *order, int n_order,
+                                         const float *weights, float *out, double *norm_sq,
+                                         void *workspace, size_t workspace_bytes,
+                                         mlf_stream stream)
+{
+    if (out == nullptr || norm_sq == nullptr) return MLF_EINVAL;
+    if (n >= 0 && (workspace == nullptr || workspace_bytes < mlf_norms_workspace_bytes(n))) return MLF_EINVAL;
+    if (reinterpret_cast<uintptr_t>(workspace) % 8 != 0 || reinterpret_cast<uintptr_t>(norm_sq) % 8 != 0) return MLF_EALIGN;
+    DenseArgs a;
+    float *written[1] = {out};
+    mlf_status st = prepare(a, update_ptrs, K, n, dtype, order, n_order, weights, written, 1);
+    if (st != MLF_OK) return st;
+    a.group_end = 0;
+    a.partials = static_cast<double *>(workspace);
+    a.model = nullptr;
+    a.momentum = nullptr;
+    a.out = out;
+    a.lr = 0.0f;
+    a.mu = 0.0f;
+    return dispatch<kAggregate, true>(a, dtype, static_cast<hipStream_t>(stream), norm_sq,
+                                      norms_partials_capacity(n));
+}
+
+extern "C" mlf_status mlf_apply_grouped_norms(float *model, float *momentum,
+                                              const void *const *update_ptrs, int K, int64_t n,
+                                              mlf_dtype dtype, const int32_t *order, int n_order,
+                                              const float *weights, const int32_t *group_len,
+                                              int n_groups, float lr, float mu, double *norms_sq,
+                                              void *workspace, size_t workspace_bytes,
+                                              mlf_stream stream)
+{
+    if (model == nullptr || norms_sq == nullptr) return MLF_EINVAL;
+    if (n_groups < 0 || (n_groups > 0 && group_len == nullptr)) return MLF_EINVAL;
+    if (n >= 0 && (workspace == nullptr || workspace_bytes < mlf_norms_workspace_bytes(n))) return MLF_EINVAL;
+    if (reinterpret_cast<uintptr_t>(workspace) % 8 != 0 || reinterpret_cast<uintptr_t>(norms_sq) % 8 != 0) return MLF_EALIGN;
+    DenseArgs a;
+    float *written[2] = {model, momentum};
+    mlf_status st = prepare(a, update_ptrs, K, n, dtype, order, n_order, weights, written, 2);
+    if (st != MLF_OK) return st;
+    long long covered = 0;
+    a.group_end = 0;
+    for (int j = 0; j < n_groups; ++j) {
+        if (group_len[j] < 1 || covered + group_len[j] > n_order) return MLF_EINVAL;
+        covered += group_len[j];
+        a.group_end |= 1ull << (covered - 1);
+    }
+    if (covered != n_order) return MLF_EINVAL;
+    a.partials = static_cast<double *>(workspace);
+    a.model = model;
+    a.momentum = momentum;
+    a.out = nullptr;
+    a.lr = lr;
+    a.mu = mu;
+    return dispatch<kApplyGrouped, true>(a, dtype, static_cast<hipStream_t>(stream), norms_sq,
+                                         norms_partials_capacity(n));
 }
 
 extern "C" const char *mlf_status_string(mlf_status status)
