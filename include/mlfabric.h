@@ -193,6 +193,23 @@ mlf_status mlf_apply_grouped_norms(float *model, float *momentum,
                                    mlf_stream stream);
 
 /*
+ * Exact server-replica divergence (Sec. 3.3 "Enforcing bounded consistency" and
+ * Sec. 5.3: the replica is kept within ||w_s - w_r||_2 <= Div_max of the server).
+ *   dist_sq[0] = sum_i (w_server[i] - w_replica[i])^2
+ * in binary64, each difference rounded once, summed in an order fixed by n, so
+ * reproducible bit for bit.  A replica catches up by applying the updates it
+ * lags by with mlf_apply_ordered / mlf_apply_grouped in the server's order; the
+ * same updates in the same order give the same model bit for bit.
+ *
+ *   w_server, w_replica  device binary32[n], read only, may be the same vector
+ *   dist_sq              device, 1 double, 8-byte aligned; written
+ *   workspace            device scratch of mlf_norms_workspace_bytes(n) bytes
+ */
+mlf_status mlf_divergence(const float *w_server, const float *w_replica, int64_t n,
+                          double *dist_sq, void *workspace, size_t workspace_bytes,
+                          mlf_stream stream);
+
+/*
  * LDA count deltas (Sec. 6 "Datasets and ML models": each LDA worker computes a
  * numerical update to the word-topic matrix).  For every triple
  * (word, topic, delta) of every buffer:

@@ -68,6 +68,9 @@ def raw():
                                             _c.c_float, _c.c_float, _c.c_void_p, _c.c_void_p,
                                             _c.c_size_t, _c.c_void_p]
     lib.mlf_apply_grouped_norms.restype = _c.c_int
+    lib.mlf_divergence.argtypes = [_c.c_void_p, _c.c_void_p, _c.c_int64, _c.c_void_p,
+                                   _c.c_void_p, _c.c_size_t, _c.c_void_p]
+    lib.mlf_divergence.restype = _c.c_int
     lib.mlf_sparse_scatter_add.argtypes = [_c.c_void_p, _c.c_void_p, _c.c_int32, _c.c_int32,
                                            vpp, _c.POINTER(_c.c_int64), _c.c_int,
                                            _c.c_void_p, _c.c_size_t, _c.c_void_p,
@@ -229,6 +232,18 @@ def mlf_apply_grouped_norms(model, momentum, updates, order, weights, group_len,
     st = raw().mlf_apply_grouped_norms(_ptr(model), _ptr(momentum), tab, K, n, kind, op, len(o),
                                        wp, gp, len(g), float(lr), float(mu), _ptr(norms_sq),
                                        _ptr(workspace), _nbytes(workspace), _stream(stream))
+    return _done(st, check)
+
+
+def mlf_divergence(w_server, w_replica, dist_sq, workspace, n=None, stream=None, check=True):
+    """dist_sq[0] = sum (w_server - w_replica)^2 (float64 device tensor)."""
+    n = w_server.numel() if n is None else int(n)
+    _state(w_server, n, "w_server")
+    _state(w_replica, n, "w_replica")
+    if dist_sq.dtype != torch.float64 or dist_sq.numel() < 1:
+        raise ValueError("dist_sq must be a float64 device tensor")
+    st = raw().mlf_divergence(_ptr(w_server), _ptr(w_replica), n, _ptr(dist_sq), _ptr(workspace),
+                              _nbytes(workspace), _stream(stream))
     return _done(st, check)
 
 

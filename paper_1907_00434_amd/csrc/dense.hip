@@ -412,6 +412,53 @@ __global__ __launch_bounds__(kFinishThreads) void norms_finish_kernel(const doub
     }
 }
 
+// Exact server-replica divergence (Sec. 3.3 / 5.3: bounded consistency keeps
+// ||w_s - w_r||_2 below Div_max): squared distance of two binary32 vectors.
+// Same reduction scheme as the norms variants: one wavefront per workgroup, a
+// pair of partial sums per workgroup (the second stays 0), fixed order.
+constexpr int kDivUnroll = 4;       // 128-bit groups per lane and vector
+
+__global__ __launch_bounds__(64) void divergence_kernel(const float *__restrict__ x,
+                                                        const float *__restrict__ y, long long n,
+                                                        long long n_vec, unsigned tiles_vec,
+                                                        double *partials)
+{
+    double sum = 0.0;
+    if (blockIdx.x < tiles_vec) {
+        const long long groups = n_vec / 4;
+        const long long base = static_cast<long long>(blockIdx.x) * 64 * kDivUnroll + threadIdx.x;
+        f32x4 a[kDivUnroll], b[kDivUnroll];
+#pragma unroll
+        for (int u = 0; u < kDivUnroll; ++u) {
+            const long long g = base + u * 64;
+            const bool ok = g < groups;
+            a[u] = ok ? __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(x) + g) : f32x4{0, 0, 0, 0};
+            b[u] = ok ? __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(y) + g) : f32x4{0, 0, 0, 0};
+        }
+#pragma unroll
+        for (int u = 0; u < kDivUnroll; ++u) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const double d = static_cast<double>(a[u][j]) - static_cast<double>(b[u][j]);
+                sum += d * d;
+            }
+        }
+    } else {
+        const long long left = n - n_vec;
+        const long long stride = static_cast<long long>(gridDim.x - tiles_vec) * 64;
+        for (long long i = static_cast<long long>(blockIdx.x - tiles_vec) * 64 + threadIdx.x; i < left;
+             i += stride) {
+            const double d = static_cast<double>(x[n_vec + i]) - static_cast<double>(y[n_vec + i]);
+            sum += d * d;
+        }
+    }
+    for (int off = 32; off > 0; off >>= 1) sum += __shfl_down(sum, off, 64);
+    if (threadIdx.x == 0) {
+        partials[2 * static_cast<size_t>(blockIdx.x)] = sum;
+        partials[2 * static_cast<size_t>(blockIdx.x) + 1] = 0.0;
+    }
+}
+
 // ---------------------------------------------------------------------------
 // Host side: validation, order applied to the pointer / weight tables, launch.
 // ---------------------------------------------------------------------------
@@ -559,6 +606,20 @@ mlf_status prepare(DenseArgs &a, const void *const *update_ptrs, int K, long lon
     return MLF_OK;
 }
 
+// The groups must tile the committed sequence: positive lengths that add up to
+// n_order.  Marks the closing position of every group in a.group_end.
+bool mark_groups(DenseArgs &a, const int32_t *group_len, int n_groups, int n_order)
+{
+    long long covered = 0;
+    a.group_end = 0;
+    for (int j = 0; j < n_groups; ++j) {
+        if (group_len[j] < 1 || covered + group_len[j] > n_order) return false;
+        covered += group_len[j];
+        a.group_end |= 1ull << (covered - 1);
+    }
+    return covered == n_order;
+}
+
 }  // namespace
 
 extern "C" mlf_status mlf_aggregate(const void *const *update_ptrs, int K, int64_t n,
@@ -638,16 +699,8 @@ extern "C" mlf_status mlf_apply_grouped(float *model, float *momentum,
     float *written[2] = {model, momentum};
     mlf_status st = prepare(a, update_ptrs, K, n, dtype, order, n_order, weights, written, 2);
     if (st != MLF_OK) return st;
-    // The groups tile the committed sequence: positive lengths that add up to it.
-    long long covered = 0;
-    a.group_end = 0;
+    if (!mark_groups(a, group_len, n_groups, n_order)) return MLF_EINVAL;
     a.partials = nullptr;
-    for (int j = 0; j < n_groups; ++j) {
-        if (group_len[j] < 1 || covered + group_len[j] > n_order) return MLF_EINVAL;
-        covered += group_len[j];
-        a.group_end |= 1ull << (covered - 1);
-    }
-    if (covered != n_order) return MLF_EINVAL;
     if (n == 0 || n_order == 0) return MLF_OK;
     a.model = model;
     a.momentum = momentum;
@@ -659,7 +712,7 @@ extern "C" mlf_status mlf_apply_grouped(float *model, float *momentum,
 
 // Partial sums a norms variant may need: one pair per workgroup of the
 // (64 lanes x 2 groups) shape, for either layout of the elements.
-size_t norms_partials_capacity(long long n)
+static size_t norms_partials_capacity(long long n)
 {
     return static_cast<size_t>(n / (64 * 2 * 4)) + 2 + static_cast<size_t>(kMaxScalarGroups);
 }
@@ -710,14 +763,7 @@ extern "C" mlf_status mlf_apply_grouped_norms(float *model, float *momentum,
     float *written[2] = {model, momentum};
     mlf_status st = prepare(a, update_ptrs, K, n, dtype, order, n_order, weights, written, 2);
     if (st != MLF_OK) return st;
-    long long covered = 0;
-    a.group_end = 0;
-    for (int j = 0; j < n_groups; ++j) {
-        if (group_len[j] < 1 || covered + group_len[j] > n_order) return MLF_EINVAL;
-        covered += group_len[j];
-        a.group_end |= 1ull << (covered - 1);
-    }
-    if (covered != n_order) return MLF_EINVAL;
+    if (!mark_groups(a, group_len, n_groups, n_order)) return MLF_EINVAL;
     a.partials = static_cast<double *>(workspace);
     a.model = model;
     a.momentum = momentum;
@@ -726,6 +772,36 @@ extern "C" mlf_status mlf_apply_grouped_norms(float *model, float *momentum,
     a.mu = mu;
     return dispatch<kApplyGrouped, true>(a, dtype, static_cast<hipStream_t>(stream), norms_sq,
                                          norms_partials_capacity(n));
+}
+
+extern "C" mlf_status mlf_divergence(const float *w_server, const float *w_replica, int64_t n,
+                                     double *dist_sq, void *workspace, size_t workspace_bytes,
+                                     mlf_stream stream)
+{
+    if (w_server == nullptr || w_replica == nullptr || dist_sq == nullptr || n < 0) return MLF_EINVAL;
+    if (workspace == nullptr || workspace_bytes < mlf_norms_workspace_bytes(n)) return MLF_EINVAL;
+    if (reinterpret_cast<uintptr_t>(w_server) % 4 != 0 || reinterpret_cast<uintptr_t>(w_replica) % 4 != 0 ||
+        reinterpret_cast<uintptr_t>(workspace) % 8 != 0 || reinterpret_cast<uintptr_t>(dist_sq) % 8 != 0) {
+        return MLF_EALIGN;
+    }
+    const bool aligned16 = reinterpret_cast<uintptr_t>(w_server) % 16 == 0 &&
+                           reinterpret_cast<uintptr_t>(w_replica) % 16 == 0;
+    const long long n_vec = aligned16 ? n / 4 * 4 : 0;
+    const long long per_tile = 64 * kDivUnroll;                      // 128-bit groups per tile
+    const long long tiles_v = (n_vec / 4 + per_tile - 1) / per_tile;
+    long long tiles_s = (n - n_vec + 63) / 64;
+    if (tiles_s > kMaxScalarGroups) tiles_s = kMaxScalarGroups;
+    if (static_cast<size_t>(tiles_v + tiles_s) > norms_partials_capacity(n)) return MLF_EUNSUPPORTED;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    double *partials = static_cast<double *>(workspace);
+    const unsigned grid = static_cast<unsigned>(tiles_v + tiles_s);
+    if (grid > 0) {
+        divergence_kernel<<<dim3(grid), dim3(64), 0, s>>>(w_server, w_replica, n, n_vec,
+                                                         static_cast<unsigned>(tiles_v), partials);
+        if (hipGetLastError() != hipSuccess) return MLF_EHIP;
+    }
+    norms_finish_kernel<<<dim3(1), dim3(kFinishThreads), 0, s>>>(partials, grid, dist_sq, 1);
+    return hipGetLastError() == hipSuccess ? MLF_OK : MLF_EHIP;
 }
 
 extern "C" const char *mlf_status_string(mlf_status status)

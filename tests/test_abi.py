@@ -24,7 +24,7 @@ def test_every_declared_symbol_is_exported():
     names = declared_functions()
     assert {"mlf_aggregate", "mlf_apply_ordered", "mlf_aggregate_apply", "mlf_apply_grouped",
             "mlf_sparse_scatter_add", "mlf_sparse_workspace_bytes", "mlf_aggregate_norm",
-            "mlf_apply_grouped_norms", "mlf_norms_workspace_bytes",
+            "mlf_apply_grouped_norms", "mlf_norms_workspace_bytes", "mlf_divergence",
             "mlf_status_string"} <= set(names)
     lib = ctypes.CDLL(mlf.library_path())
     for name in names:

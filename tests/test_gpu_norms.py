@@ -138,3 +138,54 @@ def test_norms_at_full_size_resnet_batch():
     got = norms.cpu().numpy()
     assert close(got[0], oracle.sum_sq(h_h, threads=16))
     assert close(got[1], oracle.sum_sq_diff(w_h, w0, threads=16))
+
+
+# ---- exact server-replica divergence and replica catch-up -----------------------
+
+@pytest.mark.parametrize("n", [1, 5, 1023, 1024, 1025, 70_001, 3_000_003])
+def test_divergence(n):
+    g = torch.Generator(device="cuda")
+    g.manual_seed(n)
+    a = torch.randn(n + 1, generator=g, device="cuda")
+    b = a + torch.randn(n + 1, generator=g, device="cuda") * 1e-3
+    dist = torch.full((1,), -1.0, dtype=torch.float64, device="cuda")
+    for off in (0, 1):                               # aligned, then element-wise path
+        x, y = a[off:off + n], b[off:off + n]
+        mlf.mlf_divergence(x, y, dist, workspace(n))
+        ref = oracle.sum_sq_diff(W.to_host(x), W.to_host(y), threads=8)
+        first = dist.item()
+        assert close(first, ref), (off, first, ref)
+        mlf.mlf_divergence(x, y, dist, workspace(n))
+        assert dist.item() == first
+    mlf.mlf_divergence(a, a, dist, workspace(n + 1))
+    assert dist.item() == 0.0
+
+
+def test_replica_lags_then_catches_up():
+    """Sec. 3.3: the server is two updates ahead of the replica; the divergence
+    is ||(g + g^2) h0 + (1 + g) u1 + u2||.  Replaying the same updates in the same
+    order on the replica brings it to the identical model; replaying them swapped
+    leaves gamma (u1 - u2)."""
+    cfg = W.scaled(W.CONFIGS["cfg3"], n=200_003, K=2)
+    d = W.dense_inputs(cfg, "cuda", momentum_init="random")
+    ws = workspace(cfg.n)
+    dist = torch.zeros(1, dtype=torch.float64, device="cuda")
+    w_s, h_s = d["model"].clone(), d["momentum"].clone()
+    w_r, h_r = d["model"].clone(), d["momentum"].clone()
+    mlf.mlf_apply_ordered(w_s, h_s, d["updates"], [0, 1], d["lr"], d["mu"])
+    mlf.mlf_divergence(w_s, w_r, dist, ws)
+    g, lr = np.float64(np.float32(d["mu"])), np.float64(np.float32(d["lr"]))
+    h0 = W.to_host(d["momentum"]).astype(np.float64)
+    u1 = -lr * W.to_host(d["updates"][0]).astype(np.float64)
+    u2 = -lr * W.to_host(d["updates"][1]).astype(np.float64)
+    lead = (g + g * g) * h0 + (1 + g) * u1 + u2
+    assert abs(dist.item() / float(np.sum(lead ** 2)) - 1) < 1e-4      # binary32 model rounding
+    assert close(dist.item(), oracle.sum_sq_diff(W.to_host(w_s), W.to_host(w_r)))
+    mlf.mlf_apply_ordered(w_r, h_r, d["updates"], [0, 1], d["lr"], d["mu"])   # catch up
+    mlf.mlf_divergence(w_s, w_r, dist, ws)
+    assert dist.item() == 0.0 and torch.equal(h_s, h_r)
+    w_x, h_x = d["model"].clone(), d["momentum"].clone()
+    mlf.mlf_apply_ordered(w_x, h_x, d["updates"], [1, 0], d["lr"], d["mu"])   # wrong order
+    mlf.mlf_divergence(w_s, w_x, dist, ws)
+    swapped = float(np.sum((g * (u1 - u2)) ** 2))
+    assert dist.item() > 0 and abs(dist.item() / swapped - 1) < 1e-2
