@@ -64,6 +64,9 @@ def _load():
         f.argtypes = [c.c_void_p, c.c_void_p, pp, c.c_int, c.c_int64, i32p, c.c_int,
                       f32p, i32p, c.c_int, c.c_float, c.c_float]
         f.restype = None
+    lib.orc_counts_add_dense.argtypes = [c.c_void_p, c.c_void_p, c.c_int32, c.c_int32, pp,
+                                         c.c_int, c.c_int32, c.c_int32, c.c_int32, c.c_int32]
+    lib.orc_counts_add_dense.restype = None
     lib.orc_sum_sq_f32.argtypes = [c.c_void_p, c.c_int64]
     lib.orc_sum_sq_f32.restype = c.c_double
     lib.orc_sum_sq_diff_f32.argtypes = [c.c_void_p, c.c_void_p, c.c_int64]
@@ -297,3 +300,25 @@ def scatter_add(counts, totals, V, T, triples, threads=1):
             counts.ctypes.data, tp, V, T, tab, nt, K, lo, hi, tlo, thi,
             1 if j == 0 else 0))
     return int(sum(_run(jobs, threads)))
+
+
+def counts_add_dense(counts, totals, V, T, deltas, threads=1):
+    """counts += sum of the workers' dense int32 V x T delta matrices, totals +=
+    its column sums; in place.  ``deltas`` is a list of int32 arrays of V*T."""
+    lib = _load()
+    if counts.dtype != np.int32 or counts.size != V * T or not counts.flags.c_contiguous:
+        raise ValueError("counts must be contiguous int32 with V*T entries")
+    for dm in deltas:
+        if dm.dtype != np.int32 or dm.size != V * T or not dm.flags.c_contiguous:
+            raise ValueError("each delta matrix must be contiguous int32 with V*T entries")
+    K = len(deltas)
+    tab = _ptr_table(deltas, 0) if K else (ctypes.c_void_p * 1)()
+    tp = totals.ctypes.data if totals is not None else None
+    rows = _slices(V, max(1, int(threads))) or [(0, V)]
+    cols = _slices(T, len(rows)) or [(0, T)]
+    jobs = []
+    for j, (lo, hi) in enumerate(rows):
+        tlo, thi = cols[j] if j < len(cols) else (0, 0)
+        jobs.append(lambda lo=lo, hi=hi, tlo=tlo, thi=thi: lib.orc_counts_add_dense(
+            counts.ctypes.data, tp, V, T, tab, K, lo, hi, tlo, thi))
+    _run(jobs, threads)

@@ -40,6 +40,8 @@
  *  - orc_sum_sq_*          Table 1 (push carries update_norm) and Sec. 5.3
  *                          (divergence bound from ||h||, ||u_i||; exact
  *                          divergence ||w_s - w_r||): squared 2-norms.
+ *  - orc_counts_add_dense  Sec. 6: the same LDA update exchanged as dense V x T
+ *                          delta matrices, summed over the workers.
  *  - orc_scatter_add       Sec. 6 "Datasets and ML models": an LDA worker's
  *                          update is a numerical update to the word-topic count
  *                          matrix; here it arrives as (word, topic, delta)
@@ -357,4 +359,38 @@ int64_t orc_scatter_add(int32_t *counts, int32_t *totals, int32_t V, int32_t T,
         }
     }
     return rejected;
+}
+
+/* ------------------------------------------------------------------------ */
+/* LDA update exchanged as a dense matrix (Sec. 6: every worker computes a      */
+/* numerical update to the whole word-topic matrix and the updates are summed, */
+/* as gradient updates are).  D[k] is worker k's V x T int32 delta matrix:     */
+/*   counts[w*T + t] += sum_k D[k][w*T + t] ;  totals[t] += sum_w sum_k D[k][w*T + t] */
+/* with wrap-around modulo 2^32.  A call owns the counts rows in               */
+/* [word_lo, word_hi) and the totals entries in [topic_lo, topic_hi).          */
+/* ------------------------------------------------------------------------ */
+void orc_counts_add_dense(int32_t *counts, int32_t *totals, int32_t V, int32_t T,
+                          const int32_t *const *D, int K, int32_t word_lo,
+                          int32_t word_hi, int32_t topic_lo, int32_t topic_hi)
+{
+    for (int64_t w = word_lo; w < word_hi; ++w) {
+        for (int64_t t = 0; t < T; ++t) {
+            uint32_t s = 0;
+            for (int k = 0; k < K; ++k) {
+                s += (uint32_t)D[k][w * T + t];
+            }
+            counts[w * T + t] = (int32_t)((uint32_t)counts[w * T + t] + s);
+        }
+    }
+    if (totals) {
+        for (int64_t t = topic_lo; t < topic_hi; ++t) {
+            uint32_t s = 0;
+            for (int64_t w = 0; w < V; ++w) {
+                for (int k = 0; k < K; ++k) {
+                    s += (uint32_t)D[k][w * T + t];
+                }
+            }
+            totals[t] = (int32_t)((uint32_t)totals[t] + s);
+        }
+    }
 }

@@ -123,3 +123,47 @@ def test_generator_follows_the_truncated_zipf_law():
     pmf /= pmf.sum()
     assert abs(freq[0] - pmf[0]) < 0.01 and abs(freq[:10].sum() - pmf[:10].sum()) < 0.01
     assert abs(tr[:, 2].mean()) < 0.01
+
+
+# ---- the same update exchanged as dense delta matrices (Sec. 6) ------------------
+
+def dense_deltas(cfg, triples):
+    """One V x T delta matrix per worker, built from its triples with numpy."""
+    mats = []
+    for t in triples:
+        t = t.astype(np.int64)
+        ok = (t[:, 0] >= 0) & (t[:, 0] < cfg.V) & (t[:, 1] >= 0) & (t[:, 1] < cfg.T)
+        m = np.zeros(cfg.V * cfg.T, dtype=np.int64)
+        np.add.at(m, t[ok, 0] * cfg.T + t[ok, 1], t[ok, 2])
+        mats.append(m.astype(np.int32))
+    return mats
+
+
+def test_dense_delta_sum_equals_the_triple_scatter():
+    cfg = small_cfg(m=20000)
+    counts, totals, tr = host_inputs(cfg, init="random", n_invalid=4)
+    c1, t1 = counts.copy(), totals.copy()
+    oracle.scatter_add(c1, t1, cfg.V, cfg.T, tr)
+    c2, t2 = counts.copy(), totals.copy()
+    oracle.counts_add_dense(c2, t2, cfg.V, cfg.T, dense_deltas(cfg, tr))
+    assert np.array_equal(c1, c2) and np.array_equal(t1, t2)
+    c3, t3 = counts.copy(), totals.copy()
+    oracle.counts_add_dense(c3, t3, cfg.V, cfg.T, dense_deltas(cfg, tr), threads=5)
+    assert np.array_equal(c1, c3) and np.array_equal(t1, t3)
+
+
+def test_dense_delta_sum_against_numpy_and_wraparound():
+    rng = np.random.default_rng(12)
+    V, T, K = 37, 11, 5
+    mats = [rng.integers(-2 ** 31, 2 ** 31, V * T, dtype=np.int64).astype(np.int32) for _ in range(K)]
+    counts = rng.integers(-2 ** 31, 2 ** 31, V * T, dtype=np.int64).astype(np.int32)
+    totals = rng.integers(-2 ** 31, 2 ** 31, T, dtype=np.int64).astype(np.int32)
+    total = np.sum([m.astype(np.int64) for m in mats], axis=0)
+    ref_c = ((counts.astype(np.int64) + total) & 0xFFFFFFFF).astype(np.uint32).view(np.int32)
+    ref_t = ((totals.astype(np.int64) + total.reshape(V, T).sum(axis=0)) & 0xFFFFFFFF
+             ).astype(np.uint32).view(np.int32)
+    oracle.counts_add_dense(counts, totals, V, T, mats)
+    assert np.array_equal(counts, ref_c) and np.array_equal(totals, ref_t)
+    c = np.array([1, 2], dtype=np.int32)
+    oracle.counts_add_dense(c, None, 2, 1, [])             # no workers, no totals
+    assert c.tolist() == [1, 2]
