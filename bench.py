@@ -114,6 +114,44 @@ class SparseJob:
                                         d["triples"], workspace=self.ws)
 
 
+class DivergenceJob:
+    """Exact server-replica distance of two AlexNet-sized models."""
+
+    def __init__(self, cfg, mlf, torch):
+        self.cfg, self.mlf, self.call = cfg, mlf, "divergence"
+        g = torch.Generator(device="cuda:0")
+        g.manual_seed(cfg.seed)
+        self.a = torch.randn(cfg.n, generator=g, device="cuda:0")
+        self.b = self.a + torch.randn(cfg.n, generator=g, device="cuda:0") * 1e-3
+        self.dist = torch.zeros(1, dtype=torch.float64, device="cuda:0")
+        self.ws = torch.empty(mlf.mlf_norms_workspace_bytes(cfg.n), dtype=torch.uint8, device="cuda:0")
+        self.bytes, self.units = 8 * cfg.n, cfg.n
+
+    def step(self):
+        self.mlf.mlf_divergence(self.a, self.b, self.dist, self.ws)
+
+
+class DenseDeltaJob:
+    """The LDA update as 8 dense int32 delta matrices (2 % of the cells non-zero)."""
+
+    def __init__(self, cfg, mlf, torch, K=8):
+        self.cfg, self.mlf, self.call = cfg, mlf, "counts_add_dense"
+        g = torch.Generator(device="cuda:0")
+        g.manual_seed(cfg.seed)
+        cells = cfg.V * cfg.T
+        self.mats = []
+        for _ in range(K):
+            vals = torch.randint(-5, 6, (cells,), generator=g, device="cuda:0", dtype=torch.int32)
+            keep = torch.rand(cells, generator=g, device="cuda:0") < 0.02
+            self.mats.append(torch.where(keep, vals, torch.zeros_like(vals)))
+        self.counts = torch.zeros(cells, dtype=torch.int32, device="cuda:0")
+        self.totals = torch.zeros(cfg.T, dtype=torch.int32, device="cuda:0")
+        self.bytes, self.units = (4 * K + 8) * cells, K * cells
+
+    def step(self):
+        self.mlf.mlf_counts_add_dense(self.counts, self.totals, self.cfg.V, self.cfg.T, self.mats)
+
+
 def time_steps(torch, job, steps, warmup):
     """Wall time and HIP-event time (on the launch stream) of `steps` steps."""
     for _ in range(warmup):
@@ -205,6 +243,10 @@ def main():
 
     def make(name, call=None):
         cfg = W.CONFIGS[name]
+        if call == "divergence":
+            return DivergenceJob(cfg, mlf, torch)
+        if call == "counts_add_dense":
+            return DenseDeltaJob(cfg, mlf, torch)
         if isinstance(cfg, W.SparseConfig):
             return SparseJob(cfg, mlf, W, torch)
         return DenseJob(cfg, mlf, W, torch, call)
@@ -268,8 +310,8 @@ def main():
         rows = {}
         plan = [("cfg1", None), ("cfg2", "aggregate"), ("cfg2", None), ("cfg3", None),
                 ("cfg3", "apply_grouped"), ("cfg2", "apply_grouped"),
-                ("cfg2", "apply_grouped_norms"), ("cfg3", "apply_grouped_norms"), ("cfg4", None),
-                ("cfg5", None)]
+                ("cfg2", "apply_grouped_norms"), ("cfg3", "apply_grouped_norms"),
+                ("cfg3", "divergence"), ("cfg4", None), ("cfg5", None), ("cfg5", "counts_add_dense")]
         for name, call in plan:
             j = make(name, call)
             _, ev = time_steps(torch, j, 20, 3)

@@ -253,6 +253,29 @@ mlf_status mlf_sparse_scatter_add(int32_t *counts, int32_t *totals, int32_t V,
  * than 65,536 triples, or a matrix of more than 2^29 cells. */
 size_t mlf_sparse_workspace_bytes(int32_t V, int32_t T, int64_t total_triples);
 
+/*
+ * The same LDA update exchanged as dense matrices (Sec. 6: every worker computes
+ * a numerical update to the whole word-topic matrix, and the updates are
+ * exchanged and summed like gradient updates):
+ *
+ *   counts[c] += sum_k delta_k[c]   for every cell c of the V x T matrix
+ *   totals[t] += sum_w sum_k delta_k[w*T + t]
+ *
+ * in int32 arithmetic that wraps modulo 2^32 (order-free).  Every delta matrix
+ * is read once, counts is read and written once.
+ *
+ *   counts      device int32[V*T], row-major; read and written
+ *   totals      device int32[T] or NULL
+ *   delta_ptrs  host   K device pointers to int32[V*T] matrices, 4-byte aligned
+ *                      (16-byte alignment of all pointers selects 128-bit loads)
+ *
+ * MLF_EINVAL: NULL counts / table / matrix, V < 1, T < 1, K < 0, a delta matrix
+ * overlapping counts.  K == 0 does nothing.  MLF_EUNSUPPORTED: K > MLF_MAX_K.
+ */
+mlf_status mlf_counts_add_dense(int32_t *counts, int32_t *totals, int32_t V, int32_t T,
+                                const int32_t *const *delta_ptrs, int K,
+                                mlf_stream stream);
+
 /* Static, human-readable name of a status code. */
 const char *mlf_status_string(mlf_status status);
 

@@ -14,6 +14,7 @@ from .binding import (  # noqa: F401
     mlf_aggregate_norm,
     mlf_apply_grouped,
     mlf_apply_grouped_norms,
+    mlf_counts_add_dense,
     mlf_divergence,
     mlf_norms_workspace_bytes,
     mlf_apply_ordered,

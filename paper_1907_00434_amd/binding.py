@@ -76,6 +76,9 @@ def raw():
                                            _c.c_void_p, _c.c_size_t, _c.c_void_p,
                                            _c.c_void_p]
     lib.mlf_sparse_scatter_add.restype = _c.c_int
+    lib.mlf_counts_add_dense.argtypes = [_c.c_void_p, _c.c_void_p, _c.c_int32, _c.c_int32, vpp,
+                                         _c.c_int, _c.c_void_p]
+    lib.mlf_counts_add_dense.restype = _c.c_int
     lib.mlf_sparse_workspace_bytes.argtypes = [_c.c_int32, _c.c_int32, _c.c_int64]
     lib.mlf_sparse_workspace_bytes.restype = _c.c_size_t
     lib.mlf_status_string.argtypes = [_c.c_int]
@@ -274,4 +277,20 @@ def mlf_sparse_scatter_add(counts, totals, V, T, triples, workspace=None, n_reje
     st = raw().mlf_sparse_scatter_add(_ptr(counts), _ptr(totals), int(V), int(T), tab, cnt, K,
                                       _ptr(workspace), ws_bytes, _ptr(n_rejected),
                                       _stream(stream))
+    return _done(st, check)
+
+
+def mlf_counts_add_dense(counts, totals, V, T, deltas, stream=None, check=True):
+    """counts += the sum of the workers' dense int32 V x T delta matrices and
+    totals += its column sums."""
+    if counts.dtype != torch.int32 or not counts.is_contiguous() or counts.numel() < V * T:
+        raise ValueError("counts must be contiguous int32 with V*T entries")
+    K = len(deltas)
+    tab = (_c.c_void_p * max(K, 1))()
+    for k, dm in enumerate(deltas):
+        if dm.dtype != torch.int32 or not dm.is_contiguous() or dm.numel() < V * T:
+            raise ValueError("each delta matrix must be contiguous int32 with V*T entries")
+        tab[k] = _ptr(dm)
+    st = raw().mlf_counts_add_dense(_ptr(counts), _ptr(totals), int(V), int(T), tab, K,
+                                    _stream(stream))
     return _done(st, check)

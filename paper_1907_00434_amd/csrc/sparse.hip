@@ -551,6 +551,102 @@ __global__ __launch_bounds__(kAccThreads) void accumulate_kernel(int32_t *__rest
 }
 
 // ---------------------------------------------------------------------------
+// The same LDA update exchanged as dense V x T delta matrices (Sec. 6 of the
+// paper): counts += sum over the workers, totals += its column sums.  A
+// streaming kernel like the dense float path: every delta matrix is read once
+// with 128-bit loads, counts is read and written once, each cell is owned by
+// one lane (no atomics on counts); the column sums go through the per-workgroup
+// LDS copy of the totals.
+// ---------------------------------------------------------------------------
+constexpr int kDeltaChunk = 8;          // delta matrices whose loads are in flight together
+constexpr unsigned kDeltaMaxGrid = 4096;
+
+struct DeltaArgs {
+    const int32_t *delta[MLF_MAX_K];
+    int32_t *counts;
+    int32_t *totals;
+    unsigned long long n_cells;     // V * T
+    unsigned long long n_vec;       // leading cells on the 128-bit path (0 if unaligned)
+    int K;
+    int T;
+};
+
+template <bool LDS_TOTALS>
+__device__ __forceinline__ void add_to_total(const DeltaArgs &a, int32_t *lds_totals, uint32_t col,
+                                             uint32_t v)
+{
+    if (v == 0 || a.totals == nullptr) return;
+    if constexpr (LDS_TOTALS) {
+        lds_add(&lds_totals[col], static_cast<int32_t>(v));
+    } else {
+        add_relaxed(a.totals + col, static_cast<int32_t>(v));
+    }
+}
+
+template <bool LDS_TOTALS>
+__global__ __launch_bounds__(kThreads) void dense_delta_kernel(const DeltaArgs a)
+{
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    extern __shared__ int32_t lds_totals[];
+    const uint32_t T = static_cast<uint32_t>(a.T);
+    if constexpr (LDS_TOTALS) {
+        for (uint32_t t = threadIdx.x; t < T; t += kThreads) lds_totals[t] = 0;
+        __syncthreads();
+    }
+    const unsigned long long stride = static_cast<unsigned long long>(gridDim.x) * kThreads;
+    const unsigned long long first = static_cast<unsigned long long>(blockIdx.x) * kThreads + threadIdx.x;
+
+    // 128-bit region: groups of 4 consecutive cells.
+    const unsigned long long groups = a.n_vec / 4;
+    for (unsigned long long g = first; g < groups; g += stride) {
+        u32x4 sum = {0, 0, 0, 0};
+        for (int k0 = 0; k0 < a.K; k0 += kDeltaChunk) {
+            u32x4 x[kDeltaChunk];
+#pragma unroll
+            for (int c = 0; c < kDeltaChunk; ++c) {
+                x[c] = u32x4{0, 0, 0, 0};
+                if (k0 + c < a.K) {                                  // uniform
+                    x[c] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(a.delta[k0 + c]) + g);
+                }
+            }
+#pragma unroll
+            for (int c = 0; c < kDeltaChunk; ++c) sum += x[c];
+        }
+        if ((sum.x | sum.y | sum.z | sum.w) != 0) {
+            u32x4 *dst = reinterpret_cast<u32x4 *>(a.counts) + g;
+            *dst = *dst + sum;
+            uint32_t col = static_cast<uint32_t>((g * 4) % T);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                add_to_total<LDS_TOTALS>(a, lds_totals, col, sum[j]);
+                col = col + 1 == T ? 0 : col + 1;
+            }
+        }
+    }
+    // Cell-wise region: the ragged tail, or everything when a pointer is not
+    // 16-byte aligned.
+    const unsigned long long left = a.n_cells - a.n_vec;
+    for (unsigned long long i = first; i < left; i += stride) {
+        const unsigned long long cell = a.n_vec + i;
+        uint32_t sum = 0;
+        for (int k = 0; k < a.K; ++k) sum += static_cast<uint32_t>(__builtin_nontemporal_load(a.delta[k] + cell));
+        if (sum != 0) {
+            a.counts[cell] = static_cast<int32_t>(static_cast<uint32_t>(a.counts[cell]) + sum);
+            add_to_total<LDS_TOTALS>(a, lds_totals, static_cast<uint32_t>(cell % T), sum);
+        }
+    }
+    if constexpr (LDS_TOTALS) {
+        __syncthreads();
+        if (a.totals != nullptr) {
+            for (uint32_t t = threadIdx.x; t < T; t += kThreads) {
+                const int32_t v = lds_totals[t];
+                if (v != 0) add_relaxed(a.totals + t, v);
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
 // Host side.
 // ---------------------------------------------------------------------------
 
@@ -701,5 +797,47 @@ extern "C" mlf_status mlf_sparse_scatter_add(int32_t *counts, int32_t *totals, i
     if (!launched()) return MLF_EHIP;
     const unsigned acc_items = static_cast<unsigned>(max_acc_items(total, plan.n_tiles));
     accumulate_kernel<<<dim3(acc_items), dim3(kAccThreads), 0, s>>>(counts, plan);
+    return launched() ? MLF_OK : MLF_EHIP;
+}
+
+extern "C" mlf_status mlf_counts_add_dense(int32_t *counts, int32_t *totals, int32_t V, int32_t T,
+                                           const int32_t *const *delta_ptrs, int K,
+                                           mlf_stream stream)
+{
+    if (counts == nullptr || V < 1 || T < 1 || K < 0) return MLF_EINVAL;
+    if (K > MLF_MAX_K) return MLF_EUNSUPPORTED;
+    if (K == 0) return MLF_OK;
+    if (delta_ptrs == nullptr) return MLF_EINVAL;
+    if (reinterpret_cast<uintptr_t>(counts) % 4 != 0) return MLF_EALIGN;
+    DeltaArgs a;
+    a.n_cells = static_cast<unsigned long long>(V) * static_cast<unsigned long long>(T);
+    const uintptr_t bytes = static_cast<uintptr_t>(a.n_cells) * 4;
+    const uintptr_t c_lo = reinterpret_cast<uintptr_t>(counts);
+    bool aligned16 = c_lo % 16 == 0;
+    for (int k = 0; k < K; ++k) {
+        const uintptr_t d_lo = reinterpret_cast<uintptr_t>(delta_ptrs[k]);
+        if (d_lo == 0) return MLF_EINVAL;
+        if (d_lo % 4 != 0) return MLF_EALIGN;
+        if (d_lo < c_lo + bytes && c_lo < d_lo + bytes) return MLF_EINVAL;     // overlaps counts
+        aligned16 = aligned16 && d_lo % 16 == 0;
+        a.delta[k] = delta_ptrs[k];
+    }
+    for (int k = K; k < MLF_MAX_K; ++k) a.delta[k] = nullptr;
+    a.counts = counts;
+    a.totals = totals;
+    a.n_vec = aligned16 ? a.n_cells / 4 * 4 : 0;
+    a.K = K;
+    a.T = T;
+    const unsigned long long work = a.n_vec / 4 > a.n_cells - a.n_vec ? a.n_vec / 4 : a.n_cells - a.n_vec;
+    unsigned long long tiles = (work + kThreads - 1) / kThreads;
+    if (tiles > kDeltaMaxGrid) tiles = kDeltaMaxGrid;
+    if (tiles < 1) tiles = 1;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (totals != nullptr && T <= kMaxLdsTopics) {
+        dense_delta_kernel<true><<<dim3(static_cast<unsigned>(tiles)), dim3(kThreads),
+                                   static_cast<size_t>(T) * sizeof(int32_t), s>>>(a);
+    } else {
+        dense_delta_kernel<false><<<dim3(static_cast<unsigned>(tiles)), dim3(kThreads), 0, s>>>(a);
+    }
     return launched() ? MLF_OK : MLF_EHIP;
 }

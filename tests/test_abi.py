@@ -24,7 +24,7 @@ def test_every_declared_symbol_is_exported():
     names = declared_functions()
     assert {"mlf_aggregate", "mlf_apply_ordered", "mlf_aggregate_apply", "mlf_apply_grouped",
             "mlf_sparse_scatter_add", "mlf_sparse_workspace_bytes", "mlf_aggregate_norm",
-            "mlf_apply_grouped_norms", "mlf_norms_workspace_bytes", "mlf_divergence",
+            "mlf_apply_grouped_norms", "mlf_norms_workspace_bytes", "mlf_divergence", "mlf_counts_add_dense",
             "mlf_status_string"} <= set(names)
     lib = ctypes.CDLL(mlf.library_path())
     for name in names:
@@ -131,6 +131,18 @@ def test_sparse_argument_checks():
     many = (ctypes.c_int64 * 65)(*([1] * 65))
     assert call(counts, 3, 2, tab(*([buf] * 65)), many, 65) == B.MLF_EUNSUPPORTED
     assert mlf.mlf_sparse_workspace_bytes(100000, 1000, 0) >= 0
+
+
+def test_dense_delta_argument_checks():
+    lib = B.raw()
+    counts, d0 = FAKE, FAKE + 0x100000
+    assert lib.mlf_counts_add_dense(counts, None, 3, 2, tab(d0), 0, None) == B.MLF_OK
+    assert lib.mlf_counts_add_dense(None, None, 3, 2, tab(d0), 1, None) == B.MLF_EINVAL
+    assert lib.mlf_counts_add_dense(counts, None, 0, 2, tab(d0), 1, None) == B.MLF_EINVAL
+    assert lib.mlf_counts_add_dense(counts, None, 3, 2, tab(None), 1, None) == B.MLF_EINVAL
+    assert lib.mlf_counts_add_dense(counts, None, 3, 2, tab(d0 + 2), 1, None) == B.MLF_EALIGN
+    assert lib.mlf_counts_add_dense(counts, None, 3, 2, tab(counts + 8), 1, None) == B.MLF_EINVAL
+    assert lib.mlf_counts_add_dense(counts, None, 3, 2, tab(*([d0] * 65)), 65, None) == B.MLF_EUNSUPPORTED
 
 
 def test_binding_refuses_host_tensors():

@@ -110,3 +110,73 @@ def test_many_topics_fall_back_to_global_totals(use_workspace):
     cfg = recipe(V=11, T=20_000, K=2, m=50_000)
     d = W.sparse_inputs(cfg, "cuda", init="zeros")
     run_sparse(cfg, d, use_workspace)
+
+
+# ---- the LDA update as dense delta matrices ---------------------------------------
+
+def delta_matrices(V, T, K, seed, density=0.05):
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+    mats = []
+    for _ in range(K):
+        vals = torch.randint(-5, 6, (V * T,), generator=g, device="cuda", dtype=torch.int32)
+        keep = torch.rand(V * T, generator=g, device="cuda") < density
+        mats.append(torch.where(keep, vals, torch.zeros_like(vals)).contiguous())
+    return mats
+
+
+def run_dense_delta(V, T, mats, counts, totals, threads=16):
+    import oracle
+    c_h = W.to_host(counts)
+    t_h = W.to_host(totals) if totals is not None else None
+    oracle.counts_add_dense(c_h, t_h, V, T, [W.to_host(m) for m in mats], threads=threads)
+    mlf.mlf_counts_add_dense(counts, totals, V, T, mats)
+    assert np.array_equal(counts.cpu().numpy(), c_h), "counts differ"
+    if totals is not None:
+        assert np.array_equal(totals.cpu().numpy(), t_h), "totals differ"
+
+
+@pytest.mark.parametrize("V,T,K", [(1, 1, 1), (3, 2, 2), (7, 5, 3), (301, 17, 8), (1000, 1000, 9),
+                                   (4099, 257, 17), (50, 20_000, 2), (257, 129, 64)])
+def test_dense_delta_matrices(V, T, K):
+    g = torch.Generator(device="cuda")
+    g.manual_seed(V * T + K)
+    counts = torch.randint(0, 50, (V * T,), generator=g, device="cuda", dtype=torch.int32)
+    totals = counts.view(V, T).sum(dim=0, dtype=torch.int64).to(torch.int32)
+    run_dense_delta(V, T, delta_matrices(V, T, K, seed=K), counts, totals)
+    col = counts.view(V, T).sum(dim=0, dtype=torch.int64).to(torch.int32)
+    assert torch.equal(col, totals)
+
+
+def test_dense_delta_misaligned_no_totals_and_wraparound():
+    V, T, K = 123, 45, 3
+    mats = delta_matrices(V, T + 1, K, seed=5, density=0.5)
+    views = [m[1:1 + V * T] for m in mats]                      # 4-byte aligned only
+    assert views[0].data_ptr() % 16 != 0
+    counts = torch.full((V * T,), 2 ** 31 - 3, dtype=torch.int32, device="cuda")
+    run_dense_delta(V, T, views, counts, None)
+    mlf.mlf_counts_add_dense(counts, None, V, T, [])            # no workers: nothing happens
+
+
+def test_dense_delta_equals_triple_scatter_on_the_gpu():
+    cfg = recipe(V=2003, T=300, K=4, m=100_000)
+    d = W.sparse_inputs(cfg, "cuda", init="random")
+    mats = []
+    for tr in d["triples"]:
+        m = torch.zeros(cfg.V * cfg.T, dtype=torch.int32, device="cuda")
+        m.index_put_((tr[:, 0].long() * cfg.T + tr[:, 1].long(),), tr[:, 2], accumulate=True)
+        mats.append(m)
+    c1, t1 = d["counts"].clone(), d["totals"].clone()
+    mlf.mlf_sparse_scatter_add(c1, t1, cfg.V, cfg.T, d["triples"])
+    c2, t2 = d["counts"].clone(), d["totals"].clone()
+    mlf.mlf_counts_add_dense(c2, t2, cfg.V, cfg.T, mats)
+    assert torch.equal(c1, c2) and torch.equal(t1, t2)
+
+
+def test_dense_delta_full_matrix_size():
+    """The LDA matrix of the sparse configuration (100,000 x 1,000), 8 workers."""
+    cfg = W.CONFIGS["cfg5"]
+    counts = torch.zeros(cfg.V * cfg.T, dtype=torch.int32, device="cuda")
+    totals = torch.zeros(cfg.T, dtype=torch.int32, device="cuda")
+    run_dense_delta(cfg.V, cfg.T, delta_matrices(cfg.V, cfg.T, 8, seed=11, density=0.02), counts, totals)
+    torch.cuda.empty_cache()
