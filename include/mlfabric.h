@@ -174,7 +174,7 @@ mlf_status mlf_apply_grouped(float *model, float *momentum,
  *
  *   norm_sq / norms_sq  device, 1 / 2 doubles, 8-byte aligned; written
  *   workspace           device scratch of mlf_norms_workspace_bytes(n) bytes,
- *                       8-byte aligned (MLF_EINVAL if NULL or too small)
+ *                       16-byte aligned (MLF_EINVAL if NULL or too small)
  */
 size_t mlf_norms_workspace_bytes(int64_t n);
 
@@ -203,7 +203,8 @@ mlf_status mlf_apply_grouped_norms(float *model, float *momentum,
  *
  *   w_server, w_replica  device binary32[n], read only, may be the same vector
  *   dist_sq              device, 1 double, 8-byte aligned; written
- *   workspace            device scratch of mlf_norms_workspace_bytes(n) bytes
+ *   workspace            device scratch of mlf_norms_workspace_bytes(n) bytes,
+ *                        16-byte aligned
  */
 mlf_status mlf_divergence(const float *w_server, const float *w_replica, int64_t n,
                           double *dist_sq, void *workspace, size_t workspace_bytes,

@@ -391,10 +391,22 @@ __global__ __launch_bounds__(kFinishThreads) void norms_finish_kernel(const doub
                                                                       double *out, int n_out)
 {
     __shared__ double tree[2][kFinishThreads];
+    typedef double f64x2 __attribute__((ext_vector_type(2)));
+    const f64x2 *pairs = reinterpret_cast<const f64x2 *>(partials);
     double s0 = 0.0, s1 = 0.0;
-    for (unsigned j = threadIdx.x; j < n_partials; j += kFinishThreads) {
-        s0 += partials[2 * static_cast<size_t>(j)];
-        s1 += partials[2 * static_cast<size_t>(j) + 1];
+    // Eight loads in flight per lane; the additions keep their order.
+    for (unsigned j0 = threadIdx.x; j0 < n_partials; j0 += kFinishThreads * 8) {
+        f64x2 v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const unsigned j = j0 + u * kFinishThreads;
+            v[u] = j < n_partials ? pairs[j] : f64x2{0.0, 0.0};
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            s0 += v[u].x;
+            s1 += v[u].y;
+        }
     }
     tree[0][threadIdx.x] = s0;
     tree[1][threadIdx.x] = s1;
@@ -731,7 +743,7 @@ extern "C" mlf_status mlf_aggregate_norm(const void *const *update_ptrs, int K, 
 {
     if (out == nullptr || norm_sq == nullptr) return MLF_EINVAL;
     if (n >= 0 && (workspace == nullptr || workspace_bytes < mlf_norms_workspace_bytes(n))) return MLF_EINVAL;
-    if (reinterpret_cast<uintptr_t>(workspace) % 8 != 0 || reinterpret_cast<uintptr_t>(norm_sq) % 8 != 0) return MLF_EALIGN;
+    if (reinterpret_cast<uintptr_t>(workspace) % 16 != 0 || reinterpret_cast<uintptr_t>(norm_sq) % 8 != 0) return MLF_EALIGN;
     DenseArgs a;
     float *written[1] = {out};
     mlf_status st = prepare(a, update_ptrs, K, n, dtype, order, n_order, weights, written, 1);
@@ -758,7 +770,7 @@ extern "C" mlf_status mlf_apply_grouped_norms(float *model, float *momentum,
     if (model == nullptr || norms_sq == nullptr) return MLF_EINVAL;
     if (n_groups < 0 || (n_groups > 0 && group_len == nullptr)) return MLF_EINVAL;
     if (n >= 0 && (workspace == nullptr || workspace_bytes < mlf_norms_workspace_bytes(n))) return MLF_EINVAL;
-    if (reinterpret_cast<uintptr_t>(workspace) % 8 != 0 || reinterpret_cast<uintptr_t>(norms_sq) % 8 != 0) return MLF_EALIGN;
+    if (reinterpret_cast<uintptr_t>(workspace) % 16 != 0 || reinterpret_cast<uintptr_t>(norms_sq) % 8 != 0) return MLF_EALIGN;
     DenseArgs a;
     float *written[2] = {model, momentum};
     mlf_status st = prepare(a, update_ptrs, K, n, dtype, order, n_order, weights, written, 2);
@@ -781,7 +793,7 @@ extern "C" mlf_status mlf_divergence(const float *w_server, const float *w_repli
     if (w_server == nullptr || w_replica == nullptr || dist_sq == nullptr || n < 0) return MLF_EINVAL;
     if (workspace == nullptr || workspace_bytes < mlf_norms_workspace_bytes(n)) return MLF_EINVAL;
     if (reinterpret_cast<uintptr_t>(w_server) % 4 != 0 || reinterpret_cast<uintptr_t>(w_replica) % 4 != 0 ||
-        reinterpret_cast<uintptr_t>(workspace) % 8 != 0 || reinterpret_cast<uintptr_t>(dist_sq) % 8 != 0) {
+        reinterpret_cast<uintptr_t>(workspace) % 16 != 0 || reinterpret_cast<uintptr_t>(dist_sq) % 8 != 0) {
         return MLF_EALIGN;
     }
     const bool aligned16 = reinterpret_cast<uintptr_t>(w_server) % 16 == 0 &&

@@ -558,8 +558,14 @@ __global__ __launch_bounds__(kAccThreads) void accumulate_kernel(int32_t *__rest
 // one lane (no atomics on counts); the column sums go through the per-workgroup
 // LDS copy of the totals.
 // ---------------------------------------------------------------------------
-constexpr int kDeltaChunk = 8;          // delta matrices whose loads are in flight together
-constexpr unsigned kDeltaMaxGrid = 4096;
+#ifndef MLF_DELTA_CHUNK
+#define MLF_DELTA_CHUNK 8
+#endif
+constexpr int kDeltaChunk = MLF_DELTA_CHUNK;   // delta matrices whose loads are in flight together
+#ifndef MLF_DELTA_MAX_GRID
+#define MLF_DELTA_MAX_GRID 16384
+#endif
+constexpr unsigned kDeltaMaxGrid = MLF_DELTA_MAX_GRID;
 
 struct DeltaArgs {
     const int32_t *delta[MLF_MAX_K];
