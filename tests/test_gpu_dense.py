@@ -277,3 +277,19 @@ def test_grouped_apply_full_size_alexnet_batch():
     run_dense("apply_grouped", d)
     del d
     torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("K", [16, 30])
+def test_orders_from_the_scheduling_heuristic(K):
+    """Commit orders produced the way the paper's scheduler does (shortest
+    transfer first, deadlines, look-ahead drops) instead of plain permutations."""
+    from workloads.scheduler import scheduled_order
+    for seed in (3, 4, 5):
+        cfg = recipe("cfg3", n=50_003, K=K)
+        d = W.dense_inputs(cfg, "cuda", momentum_init="random")
+        d["order"] = scheduled_order(K, seed)
+        run_dense("apply_ordered", d)
+        d["weights"] = np.full(K, 1.0 / K, np.float32)
+        M = len(d["order"])
+        d["group_len"] = [1] * (M // 3) + [M - M // 3]
+        run_dense("apply_grouped", d)
