@@ -89,6 +89,63 @@ struct Record {
     int32_t delta;
 };
 
+// Records travel through the scratch in one of two formats.  LDA deltas are
+// almost always +-1, so when every delta of the call lies in
+// [-kSmallDeltaLimit, kSmallDeltaLimit) a record is ONE word: between the two
+// partition levels the coarse range is implied by where the record lies, which
+// leaves kCoarseShift bits of cell index and the rest for the delta; after the
+// fine level only the kTileBits cell bits inside the tile are needed.  Otherwise
+// (flag raised by the first pass) records are the full 8 bytes.
+constexpr int kCoarseShift = kTileBits + kFineBits;
+constexpr int32_t kSmallDeltaLimit = 1 << (31 - kCoarseShift);
+
+template <bool WIDE>
+__device__ __forceinline__ void store_tmp(void *tmp, uint32_t i, Record r)
+{
+    if constexpr (WIDE) {
+        static_cast<Record *>(tmp)[i] = r;
+    } else {
+        static_cast<uint32_t *>(tmp)[i] =
+            (r.cell & ((1u << kCoarseShift) - 1)) | (static_cast<uint32_t>(r.delta) << kCoarseShift);
+    }
+}
+
+template <bool WIDE>
+__device__ __forceinline__ Record load_tmp(const void *tmp, uint32_t i, uint32_t coarse)
+{
+    if constexpr (WIDE) {
+        return static_cast<const Record *>(tmp)[i];
+    } else {
+        const uint32_t v = static_cast<const uint32_t *>(tmp)[i];
+        return Record{(coarse << kCoarseShift) | (v & ((1u << kCoarseShift) - 1)),
+                      static_cast<int32_t>(v) >> kCoarseShift};
+    }
+}
+
+template <bool WIDE>
+__device__ __forceinline__ void store_sorted(void *sorted, uint32_t i, Record r)
+{
+    if constexpr (WIDE) {
+        static_cast<Record *>(sorted)[i] = r;
+    } else {
+        static_cast<uint32_t *>(sorted)[i] =
+            (r.cell & (kTileCells - 1)) | (static_cast<uint32_t>(r.delta) << kTileBits);
+    }
+}
+
+// Returns the cell index inside the tile and the delta.
+template <bool WIDE>
+__device__ __forceinline__ Record load_sorted(const void *sorted, uint32_t i)
+{
+    if constexpr (WIDE) {
+        const Record r = static_cast<const Record *>(sorted)[i];
+        return Record{r.cell & (kTileCells - 1), r.delta};
+    } else {
+        const uint32_t v = static_cast<const uint32_t *>(sorted)[i];
+        return Record{v & (kTileCells - 1), static_cast<int32_t>(v) >> kTileBits};
+    }
+}
+
 // Control block of the binned path, carved out of the caller's scratch.
 struct BinPlan {
     uint32_t *hist;               // [n_tiles]   records per tile            (zeroed)
@@ -97,8 +154,9 @@ struct BinPlan {
     uint32_t *tile_start;         // [n_tiles+1] exclusive scan of hist
     uint32_t *coarse_part_start;  // [n_coarse+1] partition steps before each coarse range
     uint32_t *chunk_start;        // [n_tiles+1] accumulate work items before each tile
-    Record *tmp;                  // [n] grouped by coarse range
-    Record *sorted;               // [n] grouped by tile
+    uint32_t *wide_flag;          // [1] non-zero: some delta needs the 8-byte record (zeroed)
+    void *tmp;                    // [n] records grouped by coarse range
+    void *sorted;                 // [n] records grouped by tile
     uint32_t n_tiles;
     uint32_t n_coarse;
     unsigned long long n_cells;   // V * T
@@ -209,6 +267,7 @@ __global__ __launch_bounds__(kThreads) void scan_triples_kernel(const SparseArgs
     const long long m = a.n_triples[k];
     const long long stride = static_cast<long long>(gridDim.x) * kThreads;
     int n_bad = 0;
+    bool wide = false;
     for (long long r = static_cast<long long>(blockIdx.x) * kThreads + threadIdx.x; r < m;
          r += stride) {
         int word, topic, delta;
@@ -218,6 +277,7 @@ __global__ __launch_bounds__(kThreads) void scan_triples_kernel(const SparseArgs
         }
         const long long cell = static_cast<long long>(word) * T + topic;
         if constexpr (BINNED) {
+            wide = wide || delta < -kSmallDeltaLimit || delta >= kSmallDeltaLimit;
             wave_count(lds_hist, static_cast<uint32_t>(cell) >> kTileBits);
         } else {
             add_relaxed(a.counts + cell, delta);
@@ -244,6 +304,10 @@ __global__ __launch_bounds__(kThreads) void scan_triples_kernel(const SparseArgs
         for (uint32_t b = threadIdx.x; b < plan.n_tiles; b += kThreads) {
             const uint32_t v = lds_hist[b];
             if (v != 0) fetch_add_relaxed(plan.hist + b, v);
+        }
+        // One lane per wavefront raises the flag if any lane met a large delta.
+        if (__ballot(wide) != 0 && (threadIdx.x & 63) == 0) {
+            __hip_atomic_fetch_or(plan.wide_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
     if (a.rejected != nullptr) {
@@ -346,6 +410,7 @@ __device__ __forceinline__ uint32_t owner_of(const uint32_t *start, uint32_t n, 
 //   rec[i], live[i]  the lane's records and whether each exists
 //   digit_of(cell)   digit of a record
 //   reserve(d, n)    output index where this step's n records of digit d go
+//   emit(i, r)       writes record r at output index i
 struct PartitionLds {
     Record stage[kPartTile];
     uint32_t count[kMaxCoarse];
@@ -354,10 +419,10 @@ struct PartitionLds {
     uint32_t total;
 };
 
-template <typename DigitOf, typename Reserve>
+template <typename DigitOf, typename Reserve, typename Emit>
 __device__ __forceinline__ void partition_step(PartitionLds &s, const Record (&rec)[kPartItems],
                                                const bool (&live)[kPartItems], uint32_t n_digits,
-                                               DigitOf digit_of, Reserve reserve, Record *out)
+                                               DigitOf digit_of, Reserve reserve, Emit emit)
 {
     static_assert(kMaxCoarse == 256 && kPartThreads >= 256, "one wavefront scans 4 digits per lane");
     if (threadIdx.x < kMaxCoarse) s.count[threadIdx.x] = 0;
@@ -406,16 +471,16 @@ __device__ __forceinline__ void partition_step(PartitionLds &s, const Record (&r
     for (uint32_t i = threadIdx.x; i < total; i += kPartThreads) {
         const Record r = s.stage[i];
         const uint32_t d = digit_of(r.cell);
-        out[s.dest[d] + (i - s.offset[d])] = r;
+        emit(s.dest[d] + (i - s.offset[d]), r);
     }
 }
 
 // Coarse partition: blockIdx.y = worker buffer, blockIdx.x = step within it.
 // Valid triples become records in plan.tmp, grouped by coarse range.
-__global__ __launch_bounds__(kPartThreads) void coarse_partition_kernel(const SparseArgs a,
-                                                                    const BinPlan plan)
+template <bool WIDE>
+__device__ __forceinline__ void coarse_partition_body(PartitionLds &s, const SparseArgs &a,
+                                                      const BinPlan &plan)
 {
-    __shared__ PartitionLds s;
     const int32_t *tr = a.triples[blockIdx.y];
     const long long m = a.n_triples[blockIdx.y];
     const long long base = static_cast<long long>(blockIdx.x) * kPartTile;
@@ -434,24 +499,36 @@ __global__ __launch_bounds__(kPartThreads) void coarse_partition_kernel(const Sp
     uint32_t *cursor = plan.coarse_cursor;
     partition_step(
         s, rec, live, plan.n_coarse,
-        [](uint32_t cell) { return cell >> (kTileBits + kFineBits); },
+        [](uint32_t cell) { return cell >> kCoarseShift; },
         [=](uint32_t c, uint32_t n) {
             return tile_start[c << kFineBits] + fetch_add_relaxed(cursor + c * kCursorStride, n);
         },
-        plan.tmp);
+        [=](uint32_t i, Record r) { store_tmp<WIDE>(plan.tmp, i, r); });
+}
+
+// The record format of the call, the same for every lane (scalar register).
+__device__ __forceinline__ bool wide_records(const BinPlan &plan)
+{
+    return __builtin_amdgcn_readfirstlane(static_cast<int>(*plan.wide_flag)) != 0;
+}
+
+__global__ __launch_bounds__(kPartThreads) void coarse_partition_kernel(const SparseArgs a,
+                                                                    const BinPlan plan)
+{
+    __shared__ PartitionLds s;
+    if (wide_records(plan)) {
+        coarse_partition_body<true>(s, a, plan);
+    } else {
+        coarse_partition_body<false>(s, a, plan);
+    }
 }
 
 // Fine partition: workgroup g takes one step of one coarse range of plan.tmp
 // and writes its records to plan.sorted, grouped by tile.
-__global__ __launch_bounds__(kPartThreads) void fine_partition_kernel(const BinPlan plan)
+template <bool WIDE>
+__device__ __forceinline__ void fine_partition_body(PartitionLds &s, const BinPlan &plan, uint32_t g,
+                                                    uint32_t c)
 {
-    __shared__ PartitionLds s;
-    __shared__ uint32_t s_coarse;
-    const uint32_t g = blockIdx.x;
-    if (g >= plan.coarse_part_start[plan.n_coarse]) return;   // uniform
-    if (threadIdx.x == 0) s_coarse = owner_of(plan.coarse_part_start, plan.n_coarse, g);
-    __syncthreads();
-    const uint32_t c = s_coarse;
     const uint32_t first_tile = c << kFineBits;
     const uint32_t last_tile = min(first_tile + kFinePerCoarse, plan.n_tiles);
     const uint32_t begin = plan.tile_start[first_tile] + (g - plan.coarse_part_start[c]) * kPartTile;
@@ -462,7 +539,7 @@ __global__ __launch_bounds__(kPartThreads) void fine_partition_kernel(const BinP
     for (int i = 0; i < kPartItems; ++i) {
         const uint32_t r = begin + i * kPartThreads + threadIdx.x;
         live[i] = r < end;
-        rec[i] = live[i] ? plan.tmp[r] : Record{0u, 0};
+        rec[i] = live[i] ? load_tmp<WIDE>(plan.tmp, r, c) : Record{0u, 0};
     }
     const uint32_t *tile_start = plan.tile_start;
     uint32_t *cursor = plan.fine_cursor;
@@ -473,13 +550,48 @@ __global__ __launch_bounds__(kPartThreads) void fine_partition_kernel(const BinP
             const uint32_t tile = first_tile + f;
             return tile_start[tile] + fetch_add_relaxed(cursor + tile * kCursorStride, n);
         },
-        plan.sorted);
+        [=](uint32_t i, Record r) { store_sorted<WIDE>(plan.sorted, i, r); });
+}
+
+__global__ __launch_bounds__(kPartThreads) void fine_partition_kernel(const BinPlan plan)
+{
+    __shared__ PartitionLds s;
+    __shared__ uint32_t s_coarse;
+    const uint32_t g = blockIdx.x;
+    if (g >= plan.coarse_part_start[plan.n_coarse]) return;   // uniform
+    if (threadIdx.x == 0) s_coarse = owner_of(plan.coarse_part_start, plan.n_coarse, g);
+    __syncthreads();
+    const uint32_t c = s_coarse;
+    if (wide_records(plan)) {
+        fine_partition_body<true>(s, plan, g, c);
+    } else {
+        fine_partition_body<false>(s, plan, g, c);
+    }
 }
 
 // Accumulate: workgroup g takes up to kAccChunk records of one tile, sums them
 // into a private LDS image of the tile and merges the image into counts[].
 typedef int32_t i32x4 __attribute__((ext_vector_type(4)));
 constexpr int kAccUnroll = 8;                    // record loads in flight per lane
+
+// Adds the records [begin, end) of one tile into its LDS image.
+template <bool WIDE>
+__device__ __forceinline__ void accumulate_records(int32_t *image, const void *__restrict__ sorted,
+                                                   uint32_t begin, uint32_t end)
+{
+    for (uint32_t r0 = begin + threadIdx.x; r0 < end; r0 += kAccThreads * kAccUnroll) {
+        Record rec[kAccUnroll];
+#pragma unroll
+        for (int u = 0; u < kAccUnroll; ++u) {
+            const uint32_t r = r0 + u * kAccThreads;
+            rec[u] = r < end ? load_sorted<WIDE>(sorted, r) : Record{0u, 0};
+        }
+#pragma unroll
+        for (int u = 0; u < kAccUnroll; ++u) {
+            if (r0 + u * kAccThreads < end) lds_add(&image[rec[u].cell], rec[u].delta);
+        }
+    }
+}
 
 __global__ __launch_bounds__(kAccThreads) void accumulate_kernel(int32_t *__restrict__ counts,
                                                                  const BinPlan plan)
@@ -499,18 +611,10 @@ __global__ __launch_bounds__(kAccThreads) void accumulate_kernel(int32_t *__rest
     const uint32_t chunks = plan.chunk_start[tile + 1] - plan.chunk_start[tile];
     const uint32_t begin = plan.tile_start[tile] + (g - plan.chunk_start[tile]) * kAccChunk;
     const uint32_t end = min(begin + kAccChunk, plan.tile_start[tile + 1]);
-    const Record *__restrict__ src = plan.sorted;
-    for (uint32_t r0 = begin + threadIdx.x; r0 < end; r0 += kAccThreads * kAccUnroll) {
-        Record rec[kAccUnroll];
-#pragma unroll
-        for (int u = 0; u < kAccUnroll; ++u) {
-            const uint32_t r = r0 + u * kAccThreads;
-            rec[u] = r < end ? src[r] : Record{0u, 0};
-        }
-#pragma unroll
-        for (int u = 0; u < kAccUnroll; ++u) {
-            if (r0 + u * kAccThreads < end) lds_add(&image[rec[u].cell & (kTileCells - 1)], rec[u].delta);
-        }
+    if (wide_records(plan)) {
+        accumulate_records<true>(image, plan.sorted, begin, end);
+    } else {
+        accumulate_records<false>(image, plan.sorted, begin, end);
     }
     __syncthreads();
     const unsigned long long base = static_cast<unsigned long long>(tile) << kTileBits;
@@ -660,6 +764,12 @@ size_t align_up(size_t x) { return (x + 255) & ~static_cast<size_t>(255); }
 
 // Upper bounds of the work lists the plan kernel builds on the device: the sum
 // over ranges of ceil(n_r / step) is at most n / step + number of ranges.
+// Words cleared before every call: histogram, padded cursors, the format flag.
+size_t zeroed_words(uint32_t n_tiles, uint32_t n_coarse)
+{
+    return n_tiles + static_cast<size_t>(kCursorStride) * (n_coarse + n_tiles) + 1;
+}
+
 size_t max_fine_steps(long long n, uint32_t n_coarse) { return static_cast<size_t>(n / kPartTile) + n_coarse; }
 size_t max_acc_items(long long n, uint32_t n_tiles) { return static_cast<size_t>(n / kAccChunk) + n_tiles; }
 
@@ -681,7 +791,7 @@ size_t plan_layout(int32_t V, int32_t T, long long n, char *ws, BinPlan *plan)
         return p;
     };
     // hist, coarse_cursor, fine_cursor are contiguous: cleared by one kernel.
-    const size_t n_zeroed = n_tiles + static_cast<size_t>(kCursorStride) * (n_coarse + n_tiles);
+    const size_t n_zeroed = zeroed_words(n_tiles, n_coarse);
     char *hist = take(sizeof(uint32_t) * n_zeroed);
     char *tile_start = take(sizeof(uint32_t) * (n_tiles + 1));
     char *coarse_part_start = take(sizeof(uint32_t) * (n_coarse + 1));
@@ -692,11 +802,12 @@ size_t plan_layout(int32_t V, int32_t T, long long n, char *ws, BinPlan *plan)
         plan->hist = reinterpret_cast<uint32_t *>(hist);
         plan->coarse_cursor = plan->hist + n_tiles;
         plan->fine_cursor = plan->coarse_cursor + static_cast<size_t>(kCursorStride) * n_coarse;
+        plan->wide_flag = plan->fine_cursor + static_cast<size_t>(kCursorStride) * n_tiles;
         plan->tile_start = reinterpret_cast<uint32_t *>(tile_start);
         plan->coarse_part_start = reinterpret_cast<uint32_t *>(coarse_part_start);
         plan->chunk_start = reinterpret_cast<uint32_t *>(chunk_start);
-        plan->tmp = reinterpret_cast<Record *>(tmp);
-        plan->sorted = reinterpret_cast<Record *>(sorted);
+        plan->tmp = tmp;
+        plan->sorted = sorted;
         plan->n_tiles = n_tiles;
         plan->n_coarse = n_coarse;
         plan->n_cells = cells;
@@ -779,7 +890,7 @@ extern "C" mlf_status mlf_sparse_scatter_add(int32_t *counts, int32_t *totals, i
 
     // 1. clear the counters, 2. histogram (+ totals, rejects), 3. offsets,
     // 4. coarse partition, 5. fine partition, 6. accumulate and merge.
-    const uint32_t n_clear = plan.n_tiles + kCursorStride * (plan.n_coarse + plan.n_tiles);
+    const uint32_t n_clear = static_cast<uint32_t>(zeroed_words(plan.n_tiles, plan.n_coarse));
     clear_kernel<<<dim3((n_clear + kThreads - 1) / kThreads), dim3(kThreads), 0, s>>>(plan.hist, n_clear);
     if (!launched()) return MLF_EHIP;
     const size_t hist_lds = static_cast<size_t>(plan.n_tiles) * sizeof(uint32_t);

@@ -180,3 +180,16 @@ def test_dense_delta_full_matrix_size():
     totals = torch.zeros(cfg.T, dtype=torch.int32, device="cuda")
     run_dense_delta(cfg.V, cfg.T, delta_matrices(cfg.V, cfg.T, 8, seed=11, density=0.02), counts, totals)
     torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("big", [1023, -1024, 1024, -1025, 2 ** 30, -2 ** 31])
+def test_binned_path_record_formats(big):
+    """Deltas in [-1024, 1024) travel as 4-byte records through the scratch, any
+    other delta switches the whole call to 8-byte records: both sides of the
+    boundary, and extreme values."""
+    cfg = recipe(V=3001, T=500, K=3, m=40_000)
+    d = W.sparse_inputs(cfg, "cuda", init="random", n_invalid=3)
+    for k, tr in enumerate(d["triples"]):
+        tr[7 + k::997, 2] = big
+        tr[11 + k::1499, 2] = -big if big != -2 ** 31 else 2 ** 31 - 1
+    run_sparse(cfg, d, True)
