@@ -1,5 +1,8 @@
-// Dense hot path for gfx950: ordered K-way aggregate, ordered server apply and
-// the fused aggregate + apply, as one family of streaming kernels.
+// Dense hot path for gfx950: ordered K-way aggregate, ordered server apply, the
+// fused aggregate + apply and the grouped apply of a whole scheduled batch, as
+// one family of streaming kernels; optionally with the squared norms the
+// scheduler needs reduced in the same pass, and the exact server-replica
+// distance as a kernel of its own.
 //
 // Every element of the model is owned by exactly one lane, so the fixed
 // per-element order of the sum (Sec. 5.2 of the paper: the scheduler's order is

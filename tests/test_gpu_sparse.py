@@ -193,3 +193,29 @@ def test_binned_path_record_formats(big):
         tr[7 + k::997, 2] = big
         tr[11 + k::1499, 2] = -big if big != -2 ** 31 else 2 ** 31 - 1
     run_sparse(cfg, d, True)
+
+
+@pytest.mark.parametrize("use_workspace", [False, True])
+def test_counts_aligned_to_four_bytes_only(use_workspace):
+    """counts (and totals) that are not 16-byte aligned: the merge of the tile
+    images falls back to single cells."""
+    cfg = recipe(V=700, T=333, K=2, m=50_000)
+    d = W.sparse_inputs(cfg, "cuda", init="random")
+    big_c = torch.zeros(cfg.V * cfg.T + 3, dtype=torch.int32, device="cuda")
+    big_t = torch.zeros(cfg.T + 3, dtype=torch.int32, device="cuda")
+    big_c[1:1 + cfg.V * cfg.T] = d["counts"]
+    big_t[3:3 + cfg.T] = d["totals"]
+    d["counts"], d["totals"] = big_c[1:1 + cfg.V * cfg.T], big_t[3:3 + cfg.T]
+    assert d["counts"].data_ptr() % 16 == 4
+    counts_h, totals_h = W.to_host(d["counts"]), W.to_host(d["totals"])
+    tr_h = [W.to_host(t) for t in d["triples"]]
+    import oracle
+    oracle.scatter_add(counts_h, totals_h, cfg.V, cfg.T, tr_h)
+    ws = None
+    if use_workspace:
+        ws = torch.empty(mlf.mlf_sparse_workspace_bytes(cfg.V, cfg.T, cfg.K * cfg.m),
+                         dtype=torch.uint8, device="cuda")
+    mlf.mlf_sparse_scatter_add(d["counts"], d["totals"], cfg.V, cfg.T, d["triples"], workspace=ws)
+    assert np.array_equal(d["counts"].cpu().numpy(), counts_h)
+    assert np.array_equal(d["totals"].cpu().numpy(), totals_h)
+    assert big_c[0].item() == 0 and big_c[-2:].abs().sum().item() == 0     # nothing outside
