@@ -31,6 +31,15 @@ def test_every_declared_symbol_is_exported():
         assert hasattr(lib, name), name
 
 
+def test_header_is_plain_c():
+    """The boundary is a C header: it must compile as C99 on its own."""
+    import subprocess
+    hdr = os.path.join(ROOT, "include", "mlfabric.h")
+    res = subprocess.run(["gcc", "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror",
+                          "-fsyntax-only", "-x", "c", hdr], capture_output=True, text=True)
+    assert res.returncode == 0, res.stderr
+
+
 def test_status_strings():
     for code in (0, -1, -2, -3, -4):
         assert mlf.mlf_status_string(code).startswith("MLF_")
