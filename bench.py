@@ -33,7 +33,7 @@ MEASURED_TRAFFIC_BYTES = {
     "cfg2": 2044.7e6,
     "cfg3": 8798.6e6,
     "cfg4": 4427.5e6,
-    "cfg5": 4319.0e6,
+    "cfg5": 3295.9e6,
 }
 
 
