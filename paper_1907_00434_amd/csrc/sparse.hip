@@ -52,6 +52,7 @@ constexpr int kFineBits = MLF_FINE_BITS;         // log2 of the fine tiles per c
 constexpr uint32_t kFinePerCoarse = 1u << kFineBits;
 constexpr uint32_t kMaxCoarse = 256;             // coarse ranges (one counter per lane)
 constexpr uint32_t kMaxTiles = 16384;            // tiles a call may span (LDS histogram, scan)
+constexpr uint32_t kHotWords = kMaxTiles / 32;   // words of the hot-tile bitmap
 #ifndef MLF_PART_THREADS
 #define MLF_PART_THREADS 512
 #endif
@@ -154,6 +155,10 @@ struct BinPlan {
     uint32_t *tile_start;         // [n_tiles+1] exclusive scan of hist
     uint32_t *coarse_part_start;  // [n_coarse+1] partition steps before each coarse range
     uint32_t *chunk_start;        // [n_tiles+1] accumulate work items before each tile
+    uint32_t *tmp_start;          // [n_coarse+1] first record of each coarse range in tmp
+    uint32_t *hot_tile;           // [kMaxCoarse] tile of each "hot" digit of the coarse level
+    uint32_t *hot_bits;           // [kHotWords] bit b set = tile b is hot
+    uint32_t *hot_before;         // [kHotWords] hot tiles before the first tile of each word
     uint32_t *wide_flag;          // [1] non-zero: some delta needs the 8-byte record (zeroed)
     void *tmp;                    // [n] records grouped by coarse range
     void *sorted;                 // [n] records grouped by tile
@@ -362,24 +367,97 @@ __device__ void block_exclusive_scan(uint32_t n, F value, uint32_t *out, uint32_
 }
 
 // One workgroup: turns the tile histogram into the offsets every later step uses.
+//
+// Heavy tiles skip the fine level.  The coarse level has kMaxCoarse digits and
+// needs n_coarse of them for the coarse ranges; each spare digit is given to one
+// of the heaviest tiles ("hot"), whose records the coarse level then writes
+// straight to their final place in `sorted`.  Under a Zipf law a few hundred
+// tiles hold most of the records, so most records are moved once instead of
+// twice.  The hot tiles are those with at least `threshold` records, the
+// smallest power-of-two fraction of the total that leaves no more hot tiles
+// than spare digits.  They are published as a bitmap plus, per bitmap word, the
+// number of hot tiles before it, so that a lane finds the digit of a tile with
+// two LDS reads and a population count.
+constexpr int kHotShifts = 24;
+
 __global__ __launch_bounds__(kScanThreads) void plan_kernel(const BinPlan plan)
 {
     __shared__ uint32_t scratch[kScanThreads];
+    __shared__ uint32_t tiles_at_least[kHotShifts];
+    __shared__ uint32_t hot_in_range[kMaxCoarse];     // hot records per coarse range
+    __shared__ uint32_t s_threshold;
     const uint32_t *hist = plan.hist;
-    block_exclusive_scan(plan.n_tiles, [=](uint32_t j) { return hist[j]; }, plan.tile_start,
-                         scratch);
+    const uint32_t n_tiles = plan.n_tiles;
+    const uint32_t n_coarse = plan.n_coarse;
+    block_exclusive_scan(n_tiles, [=](uint32_t j) { return hist[j]; }, plan.tile_start, scratch);
     __threadfence_block();
     const uint32_t *tile_start = plan.tile_start;
-    const uint32_t n_tiles = plan.n_tiles;
+    const uint32_t total = tile_start[n_tiles];
+
+    // Threshold of the hot tiles.  (All tile loops below run whole wavefronts.)
+    if (threadIdx.x < kHotShifts) tiles_at_least[threadIdx.x] = 0;
+    if (threadIdx.x < kMaxCoarse) hot_in_range[threadIdx.x] = 0;
+    __syncthreads();
+    for (uint32_t base = 0; base < n_tiles; base += kScanThreads) {
+        const uint32_t b = base + threadIdx.x;
+        const uint32_t h = b < n_tiles ? hist[b] : 0u;
+        for (int j = 0; j < kHotShifts; ++j) {
+            const unsigned long long heavy = __ballot(h != 0 && h >= (total >> j));
+            if ((threadIdx.x & 63) == 0 && heavy != 0) {
+                lds_fetch_add(&tiles_at_least[j], static_cast<uint32_t>(__popcll(heavy)));
+            }
+        }
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const uint32_t spare = kMaxCoarse - n_coarse;
+        uint32_t threshold = 0xffffffffu;                    // no hot tile
+        for (int j = 0; j < kHotShifts; ++j) {
+            if (tiles_at_least[j] <= spare && (total >> j) >= 1) threshold = total >> j;
+        }
+        s_threshold = threshold;
+    }
+    __syncthreads();
+    const uint32_t threshold = s_threshold;
+
+    // Bitmap of the hot tiles (all kHotWords words are written) and the hot
+    // records of every coarse range.
+    for (uint32_t base = 0; base < kMaxTiles; base += kScanThreads) {
+        const uint32_t b = base + threadIdx.x;
+        const uint32_t h = b < n_tiles ? hist[b] : 0u;
+        const bool hot = h != 0 && h >= threshold;
+        const unsigned long long mask = __ballot(hot);
+        if ((threadIdx.x & 63) == 0) {
+            plan.hot_bits[b >> 5] = static_cast<uint32_t>(mask);
+            plan.hot_bits[(b >> 5) + 1] = static_cast<uint32_t>(mask >> 32);
+        }
+        if (hot) lds_fetch_add(&hot_in_range[b >> kFineBits], h);
+    }
+    __syncthreads();
+    __threadfence_block();
+    const uint32_t *hot_bits = plan.hot_bits;
+    block_exclusive_scan(kHotWords, [=](uint32_t w) { return static_cast<uint32_t>(__popc(hot_bits[w])); },
+                         plan.hot_before, scratch);
+    __threadfence_block();
+    // Tile of every hot digit.
+    for (uint32_t b = threadIdx.x; b < n_tiles; b += kScanThreads) {
+        const uint32_t word = hot_bits[b >> 5];
+        if ((word >> (b & 31)) & 1u) {
+            const uint32_t slot = plan.hot_before[b >> 5] + __popc(word & ((1u << (b & 31)) - 1u));
+            plan.hot_tile[slot] = b;
+        }
+    }
+
+    // Records of each coarse range that still go through the fine level.
+    auto cold_records = [&](uint32_t c) {
+        const uint32_t lo = c << kFineBits;
+        const uint32_t hi = min(lo + kFinePerCoarse, n_tiles);
+        return tile_start[hi] - tile_start[lo] - hot_in_range[c];
+    };
+    block_exclusive_scan(n_coarse, cold_records, plan.tmp_start, scratch);
     // Partition steps (kPartTile records each) per coarse range.
     block_exclusive_scan(
-        plan.n_coarse,
-        [=](uint32_t c) {
-            const uint32_t lo = c << kFineBits;
-            const uint32_t hi = min(lo + kFinePerCoarse, n_tiles);
-            const uint32_t cnt = tile_start[hi] - tile_start[lo];
-            return (cnt + kPartTile - 1) / kPartTile;
-        },
+        n_coarse, [&](uint32_t c) { return (cold_records(c) + kPartTile - 1) / kPartTile; },
         plan.coarse_part_start, scratch);
     // Accumulate work items (kAccChunk records each) per tile.
     block_exclusive_scan(
@@ -404,13 +482,12 @@ __device__ __forceinline__ uint32_t owner_of(const uint32_t *start, uint32_t n, 
 }
 
 // One partition step of a workgroup: up to kPartTile records held in registers
-// are grouped by `digit` (n_digits <= kMaxCoarse) in LDS and written out so that
-// the records of one digit form one contiguous run at the place reserved for
-// them in the output.
+// are grouped by digit (< kMaxCoarse) in LDS and written out so that the records
+// of one digit form one contiguous run at the place reserved for them.
 //   rec[i], live[i]  the lane's records and whether each exists
 //   digit_of(cell)   digit of a record
 //   reserve(d, n)    output index where this step's n records of digit d go
-//   emit(i, r)       writes record r at output index i
+//   emit(d, i, r)    writes record r of digit d at output index i
 struct PartitionLds {
     Record stage[kPartTile];
     uint32_t count[kMaxCoarse];
@@ -421,16 +498,15 @@ struct PartitionLds {
 
 template <typename DigitOf, typename Reserve, typename Emit>
 __device__ __forceinline__ void partition_step(PartitionLds &s, const Record (&rec)[kPartItems],
-                                               const bool (&live)[kPartItems], uint32_t n_digits,
-                                               DigitOf digit_of, Reserve reserve, Emit emit)
+                                               const bool (&live)[kPartItems], DigitOf digit_of,
+                                               Reserve reserve, Emit emit)
 {
     static_assert(kMaxCoarse == 256 && kPartThreads >= 256, "one wavefront scans 4 digits per lane");
-    if (threadIdx.x < kMaxCoarse) s.count[threadIdx.x] = 0;
-    __syncthreads();
-    uint32_t rank[kPartItems];
+    uint32_t dig[kPartItems], rank[kPartItems];
 #pragma unroll
     for (int i = 0; i < kPartItems; ++i) {
-        rank[i] = wave_rank(s.count, digit_of(rec[i].cell), live[i]);
+        dig[i] = live[i] ? digit_of(rec[i].cell) : 0u;
+        rank[i] = wave_rank(s.count, dig[i], live[i]);
     }
     __syncthreads();
     if (threadIdx.x < 64) {
@@ -457,29 +533,35 @@ __device__ __forceinline__ void partition_step(PartitionLds &s, const Record (&r
         }
         if (lane == 63) s.total = incl;
     }
-    if (threadIdx.x < n_digits) {
+    if (threadIdx.x < kMaxCoarse) {
         const uint32_t mine = s.count[threadIdx.x];
         if (mine != 0) s.dest[threadIdx.x] = reserve(threadIdx.x, mine);
     }
     __syncthreads();
 #pragma unroll
     for (int i = 0; i < kPartItems; ++i) {
-        if (live[i]) s.stage[s.offset[digit_of(rec[i].cell)] + rank[i]] = rec[i];
+        if (live[i]) s.stage[s.offset[dig[i]] + rank[i]] = rec[i];
     }
     __syncthreads();
     const uint32_t total = s.total;
     for (uint32_t i = threadIdx.x; i < total; i += kPartThreads) {
         const Record r = s.stage[i];
         const uint32_t d = digit_of(r.cell);
-        emit(s.dest[d] + (i - s.offset[d]), r);
+        emit(d, s.dest[d] + (i - s.offset[d]), r);
     }
 }
 
 // Coarse partition: blockIdx.y = worker buffer, blockIdx.x = step within it.
-// Valid triples become records in plan.tmp, grouped by coarse range.
+// Valid triples become records: those of hot tiles go to their final place in
+// plan.sorted, the others to plan.tmp, grouped by coarse range.
+struct HotLds {
+    uint32_t bits[kHotWords];
+    uint16_t before[kHotWords];
+};
+
 template <bool WIDE>
-__device__ __forceinline__ void coarse_partition_body(PartitionLds &s, const SparseArgs &a,
-                                                      const BinPlan &plan)
+__device__ __forceinline__ void coarse_partition_body(PartitionLds &s, HotLds &hot,
+                                                      const SparseArgs &a, const BinPlan &plan)
 {
     const int32_t *tr = a.triples[blockIdx.y];
     const long long m = a.n_triples[blockIdx.y];
@@ -495,15 +577,41 @@ __device__ __forceinline__ void coarse_partition_body(PartitionLds &s, const Spa
         rec[i].cell = static_cast<uint32_t>(static_cast<long long>(word) * a.T + topic);
         rec[i].delta = delta;
     }
-    const uint32_t *tile_start = plan.tile_start;
-    uint32_t *cursor = plan.coarse_cursor;
+    // The hot-tile bitmap and the digit counters, while the triples are in flight.
+    static_assert(kHotWords <= kPartThreads && kMaxCoarse <= kPartThreads, "one word per lane");
+    if (threadIdx.x < kHotWords) {
+        hot.bits[threadIdx.x] = plan.hot_bits[threadIdx.x];
+        hot.before[threadIdx.x] = static_cast<uint16_t>(plan.hot_before[threadIdx.x]);
+    }
+    if (threadIdx.x < kMaxCoarse) s.count[threadIdx.x] = 0;
+    __syncthreads();
+    const uint32_t n_coarse = plan.n_coarse;
+    const HotLds *h = &hot;
     partition_step(
-        s, rec, live, plan.n_coarse,
-        [](uint32_t cell) { return cell >> kCoarseShift; },
-        [=](uint32_t c, uint32_t n) {
-            return tile_start[c << kFineBits] + fetch_add_relaxed(cursor + c * kCursorStride, n);
+        s, rec, live,
+        [=](uint32_t cell) {
+            const uint32_t tile = cell >> kTileBits;
+            const uint32_t word = h->bits[tile >> 5];
+            const uint32_t bit = tile & 31;
+            if ((word >> bit) & 1u) {
+                return n_coarse + h->before[tile >> 5] + static_cast<uint32_t>(__popc(word & ((1u << bit) - 1u)));
+            }
+            return tile >> kFineBits;
         },
-        [=](uint32_t i, Record r) { store_tmp<WIDE>(plan.tmp, i, r); });
+        [=](uint32_t d, uint32_t n) {
+            if (d < n_coarse) {
+                return plan.tmp_start[d] + fetch_add_relaxed(plan.coarse_cursor + d * kCursorStride, n);
+            }
+            const uint32_t tile = plan.hot_tile[d - n_coarse];
+            return plan.tile_start[tile] + fetch_add_relaxed(plan.fine_cursor + tile * kCursorStride, n);
+        },
+        [=](uint32_t d, uint32_t i, Record r) {
+            if (d < n_coarse) {
+                store_tmp<WIDE>(plan.tmp, i, r);
+            } else {
+                store_sorted<WIDE>(plan.sorted, i, r);
+            }
+        });
 }
 
 // The record format of the call, the same for every lane (scalar register).
@@ -516,10 +624,11 @@ __global__ __launch_bounds__(kPartThreads) void coarse_partition_kernel(const Sp
                                                                     const BinPlan plan)
 {
     __shared__ PartitionLds s;
+    __shared__ HotLds hot;
     if (wide_records(plan)) {
-        coarse_partition_body<true>(s, a, plan);
+        coarse_partition_body<true>(s, hot, a, plan);
     } else {
-        coarse_partition_body<false>(s, a, plan);
+        coarse_partition_body<false>(s, hot, a, plan);
     }
 }
 
@@ -530,9 +639,8 @@ __device__ __forceinline__ void fine_partition_body(PartitionLds &s, const BinPl
                                                     uint32_t c)
 {
     const uint32_t first_tile = c << kFineBits;
-    const uint32_t last_tile = min(first_tile + kFinePerCoarse, plan.n_tiles);
-    const uint32_t begin = plan.tile_start[first_tile] + (g - plan.coarse_part_start[c]) * kPartTile;
-    const uint32_t end = min(begin + kPartTile, plan.tile_start[last_tile]);
+    const uint32_t begin = plan.tmp_start[c] + (g - plan.coarse_part_start[c]) * kPartTile;
+    const uint32_t end = min(begin + kPartTile, plan.tmp_start[c + 1]);
     Record rec[kPartItems];
     bool live[kPartItems];
 #pragma unroll
@@ -541,16 +649,15 @@ __device__ __forceinline__ void fine_partition_body(PartitionLds &s, const BinPl
         live[i] = r < end;
         rec[i] = live[i] ? load_tmp<WIDE>(plan.tmp, r, c) : Record{0u, 0};
     }
-    const uint32_t *tile_start = plan.tile_start;
-    uint32_t *cursor = plan.fine_cursor;
+    if (threadIdx.x < kMaxCoarse) s.count[threadIdx.x] = 0;
+    __syncthreads();
     partition_step(
-        s, rec, live, kFinePerCoarse,
-        [](uint32_t cell) { return (cell >> kTileBits) & (kFinePerCoarse - 1); },
+        s, rec, live, [](uint32_t cell) { return (cell >> kTileBits) & (kFinePerCoarse - 1); },
         [=](uint32_t f, uint32_t n) {
             const uint32_t tile = first_tile + f;
-            return tile_start[tile] + fetch_add_relaxed(cursor + tile * kCursorStride, n);
+            return plan.tile_start[tile] + fetch_add_relaxed(plan.fine_cursor + tile * kCursorStride, n);
         },
-        [=](uint32_t i, Record r) { store_sorted<WIDE>(plan.sorted, i, r); });
+        [=](uint32_t, uint32_t i, Record r) { store_sorted<WIDE>(plan.sorted, i, r); });
 }
 
 __global__ __launch_bounds__(kPartThreads) void fine_partition_kernel(const BinPlan plan)
@@ -796,6 +903,10 @@ size_t plan_layout(int32_t V, int32_t T, long long n, char *ws, BinPlan *plan)
     char *tile_start = take(sizeof(uint32_t) * (n_tiles + 1));
     char *coarse_part_start = take(sizeof(uint32_t) * (n_coarse + 1));
     char *chunk_start = take(sizeof(uint32_t) * (n_tiles + 1));
+    char *tmp_start = take(sizeof(uint32_t) * (n_coarse + 1));
+    char *hot_tile = take(sizeof(uint32_t) * kMaxCoarse);
+    char *hot_bits = take(sizeof(uint32_t) * (kHotWords + 1));
+    char *hot_before = take(sizeof(uint32_t) * (kHotWords + 1));
     char *tmp = take(sizeof(Record) * static_cast<size_t>(n));
     char *sorted = take(sizeof(Record) * static_cast<size_t>(n));
     if (plan != nullptr) {
@@ -806,6 +917,10 @@ size_t plan_layout(int32_t V, int32_t T, long long n, char *ws, BinPlan *plan)
         plan->tile_start = reinterpret_cast<uint32_t *>(tile_start);
         plan->coarse_part_start = reinterpret_cast<uint32_t *>(coarse_part_start);
         plan->chunk_start = reinterpret_cast<uint32_t *>(chunk_start);
+        plan->tmp_start = reinterpret_cast<uint32_t *>(tmp_start);
+        plan->hot_tile = reinterpret_cast<uint32_t *>(hot_tile);
+        plan->hot_bits = reinterpret_cast<uint32_t *>(hot_bits);
+        plan->hot_before = reinterpret_cast<uint32_t *>(hot_before);
         plan->tmp = tmp;
         plan->sorted = sorted;
         plan->n_tiles = n_tiles;
