@@ -33,7 +33,7 @@ MEASURED_TRAFFIC_BYTES = {
     "cfg2": 2044.7e6,
     "cfg3": 8798.6e6,
     "cfg4": 4427.5e6,
-    "cfg5": 3295.9e6,
+    "cfg5": 2848.4e6,
 }
 
 
@@ -46,6 +46,8 @@ def parse_args():
     ap.add_argument("--no-rows", action="store_true",
                     help="skip the extra per-call measurements of the other configurations")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--permute-ids", action="store_true",
+                    help="cfg5: word ids are a seeded permutation of the Zipf ranks")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy a few times (reference for "
                          "hardware byte counters)")
@@ -97,10 +99,10 @@ class DenseJob:
 
 
 class SparseJob:
-    def __init__(self, cfg, mlf, W, torch):
+    def __init__(self, cfg, mlf, W, torch, permute_ids=False):
         self.cfg, self.mlf = cfg, mlf
-        self.call = "sparse_scatter_add"
-        self.d = W.sparse_inputs(cfg, "cuda:0")
+        self.call = "sparse_scatter_add" + (" (permuted word ids)" if permute_ids else "")
+        self.d = W.sparse_inputs(cfg, "cuda:0", permute_ids=permute_ids)
         total = cfg.K * cfg.m
         nbytes = mlf.mlf_sparse_workspace_bytes(cfg.V, cfg.T, total)
         self.ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device="cuda:0")
@@ -176,7 +178,7 @@ def cpu_baseline(job, W, torch):
     import oracle
     threads = min(16, len(os.sched_getaffinity(0)))
     cfg, d = job.cfg, job.d
-    if job.call == "sparse_scatter_add":
+    if job.call.startswith("sparse_scatter_add"):
         tr = [W.to_host(t[: 500_000]) for t in d["triples"][:8]]
         counts = np.zeros(cfg.V * cfg.T, dtype=np.int32)
         totals = np.zeros(cfg.T, dtype=np.int32)
@@ -248,7 +250,7 @@ def main():
         if call == "counts_add_dense":
             return DenseDeltaJob(cfg, mlf, torch)
         if isinstance(cfg, W.SparseConfig):
-            return SparseJob(cfg, mlf, W, torch)
+            return SparseJob(cfg, mlf, W, torch, permute_ids=(call == "permuted" or args.permute_ids))
         return DenseJob(cfg, mlf, W, torch, call)
 
     job = make(args.workload)
@@ -311,7 +313,7 @@ def main():
         plan = [("cfg1", None), ("cfg2", "aggregate"), ("cfg2", None), ("cfg3", None),
                 ("cfg3", "apply_grouped"), ("cfg2", "apply_grouped"),
                 ("cfg2", "apply_grouped_norms"), ("cfg3", "apply_grouped_norms"),
-                ("cfg3", "divergence"), ("cfg4", None), ("cfg5", None), ("cfg5", "counts_add_dense")]
+                ("cfg3", "divergence"), ("cfg4", None), ("cfg5", None), ("cfg5", "permuted"), ("cfg5", "counts_add_dense")]
         for name, call in plan:
             j = make(name, call)
             _, ev = time_steps(torch, j, 20, 3)

@@ -54,7 +54,7 @@ constexpr uint32_t kMaxCoarse = 256;             // coarse ranges (one counter p
 constexpr uint32_t kMaxTiles = 16384;            // tiles a call may span (LDS histogram, scan)
 constexpr uint32_t kHotWords = kMaxTiles / 32;   // words of the hot-tile bitmap
 #ifndef MLF_PART_THREADS
-#define MLF_PART_THREADS 512
+#define MLF_PART_THREADS 1024
 #endif
 #ifndef MLF_CURSOR_STRIDE
 #define MLF_CURSOR_STRIDE 32
@@ -150,13 +150,15 @@ __device__ __forceinline__ Record load_sorted(const void *sorted, uint32_t i)
 // Control block of the binned path, carved out of the caller's scratch.
 struct BinPlan {
     uint32_t *hist;               // [n_tiles]   records per tile            (zeroed)
-    uint32_t *coarse_cursor;      // [n_coarse * kCursorStride] records placed so far (zeroed)
+    uint32_t *coarse_cursor;      // [kMaxCoarse * kCursorStride] records placed so far per digit of the
+                                  //                             coarse level (zeroed)
     uint32_t *fine_cursor;        // [n_tiles * kCursorStride]  records placed so far (zeroed)
     uint32_t *tile_start;         // [n_tiles+1] exclusive scan of hist
     uint32_t *coarse_part_start;  // [n_coarse+1] partition steps before each coarse range
     uint32_t *chunk_start;        // [n_tiles+1] accumulate work items before each tile
     uint32_t *tmp_start;          // [n_coarse+1] first record of each coarse range in tmp
-    uint32_t *hot_tile;           // [kMaxCoarse] tile of each "hot" digit of the coarse level
+    uint32_t *digit_start;        // [kMaxCoarse] first output index of each digit of the coarse level:
+                                  //              in tmp for a coarse range, in sorted for a hot tile
     uint32_t *hot_bits;           // [kHotWords] bit b set = tile b is hot
     uint32_t *hot_before;         // [kHotWords] hot tiles before the first tile of each word
     uint32_t *wide_flag;          // [1] non-zero: some delta needs the 8-byte record (zeroed)
@@ -378,7 +380,10 @@ __device__ void block_exclusive_scan(uint32_t n, F value, uint32_t *out, uint32_
 // than spare digits.  They are published as a bitmap plus, per bitmap word, the
 // number of hot tiles before it, so that a lane finds the digit of a tile with
 // two LDS reads and a population count.
-constexpr int kHotShifts = 24;
+#ifndef MLF_HOT_SHIFTS
+#define MLF_HOT_SHIFTS 24
+#endif
+constexpr int kHotShifts = MLF_HOT_SHIFTS;     // a hot tile holds at least total >> (kHotShifts - 1) records
 
 __global__ __launch_bounds__(kScanThreads) void plan_kernel(const BinPlan plan)
 {
@@ -439,12 +444,13 @@ __global__ __launch_bounds__(kScanThreads) void plan_kernel(const BinPlan plan)
     block_exclusive_scan(kHotWords, [=](uint32_t w) { return static_cast<uint32_t>(__popc(hot_bits[w])); },
                          plan.hot_before, scratch);
     __threadfence_block();
-    // Tile of every hot digit.
+    // Hot digits follow the coarse ranges, in tile order; their records go to
+    // the tile's place in `sorted`.
     for (uint32_t b = threadIdx.x; b < n_tiles; b += kScanThreads) {
         const uint32_t word = hot_bits[b >> 5];
         if ((word >> (b & 31)) & 1u) {
             const uint32_t slot = plan.hot_before[b >> 5] + __popc(word & ((1u << (b & 31)) - 1u));
-            plan.hot_tile[slot] = b;
+            plan.digit_start[n_coarse + slot] = tile_start[b];
         }
     }
 
@@ -455,6 +461,8 @@ __global__ __launch_bounds__(kScanThreads) void plan_kernel(const BinPlan plan)
         return tile_start[hi] - tile_start[lo] - hot_in_range[c];
     };
     block_exclusive_scan(n_coarse, cold_records, plan.tmp_start, scratch);
+    __threadfence_block();
+    for (uint32_t c = threadIdx.x; c < n_coarse; c += kScanThreads) plan.digit_start[c] = plan.tmp_start[c];
     // Partition steps (kPartTile records each) per coarse range.
     block_exclusive_scan(
         n_coarse, [&](uint32_t c) { return (cold_records(c) + kPartTile - 1) / kPartTile; },
@@ -599,11 +607,7 @@ __device__ __forceinline__ void coarse_partition_body(PartitionLds &s, HotLds &h
             return tile >> kFineBits;
         },
         [=](uint32_t d, uint32_t n) {
-            if (d < n_coarse) {
-                return plan.tmp_start[d] + fetch_add_relaxed(plan.coarse_cursor + d * kCursorStride, n);
-            }
-            const uint32_t tile = plan.hot_tile[d - n_coarse];
-            return plan.tile_start[tile] + fetch_add_relaxed(plan.fine_cursor + tile * kCursorStride, n);
+            return plan.digit_start[d] + fetch_add_relaxed(plan.coarse_cursor + d * kCursorStride, n);
         },
         [=](uint32_t d, uint32_t i, Record r) {
             if (d < n_coarse) {
@@ -874,7 +878,7 @@ size_t align_up(size_t x) { return (x + 255) & ~static_cast<size_t>(255); }
 // Words cleared before every call: histogram, padded cursors, the format flag.
 size_t zeroed_words(uint32_t n_tiles, uint32_t n_coarse)
 {
-    return n_tiles + static_cast<size_t>(kCursorStride) * (n_coarse + n_tiles) + 1;
+    return n_tiles + static_cast<size_t>(kCursorStride) * (kMaxCoarse + n_tiles) + 1;
 }
 
 size_t max_fine_steps(long long n, uint32_t n_coarse) { return static_cast<size_t>(n / kPartTile) + n_coarse; }
@@ -904,7 +908,7 @@ size_t plan_layout(int32_t V, int32_t T, long long n, char *ws, BinPlan *plan)
     char *coarse_part_start = take(sizeof(uint32_t) * (n_coarse + 1));
     char *chunk_start = take(sizeof(uint32_t) * (n_tiles + 1));
     char *tmp_start = take(sizeof(uint32_t) * (n_coarse + 1));
-    char *hot_tile = take(sizeof(uint32_t) * kMaxCoarse);
+    char *digit_start = take(sizeof(uint32_t) * kMaxCoarse);
     char *hot_bits = take(sizeof(uint32_t) * (kHotWords + 1));
     char *hot_before = take(sizeof(uint32_t) * (kHotWords + 1));
     char *tmp = take(sizeof(Record) * static_cast<size_t>(n));
@@ -912,13 +916,13 @@ size_t plan_layout(int32_t V, int32_t T, long long n, char *ws, BinPlan *plan)
     if (plan != nullptr) {
         plan->hist = reinterpret_cast<uint32_t *>(hist);
         plan->coarse_cursor = plan->hist + n_tiles;
-        plan->fine_cursor = plan->coarse_cursor + static_cast<size_t>(kCursorStride) * n_coarse;
+        plan->fine_cursor = plan->coarse_cursor + static_cast<size_t>(kCursorStride) * kMaxCoarse;
         plan->wide_flag = plan->fine_cursor + static_cast<size_t>(kCursorStride) * n_tiles;
         plan->tile_start = reinterpret_cast<uint32_t *>(tile_start);
         plan->coarse_part_start = reinterpret_cast<uint32_t *>(coarse_part_start);
         plan->chunk_start = reinterpret_cast<uint32_t *>(chunk_start);
         plan->tmp_start = reinterpret_cast<uint32_t *>(tmp_start);
-        plan->hot_tile = reinterpret_cast<uint32_t *>(hot_tile);
+        plan->digit_start = reinterpret_cast<uint32_t *>(digit_start);
         plan->hot_bits = reinterpret_cast<uint32_t *>(hot_bits);
         plan->hot_before = reinterpret_cast<uint32_t *>(hot_before);
         plan->tmp = tmp;
