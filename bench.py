@@ -171,6 +171,23 @@ def time_steps(torch, job, steps, warmup):
     return wall_ms, event_ms
 
 
+def time_each(torch, job, steps, between=None):
+    """Median and minimum HIP-event time of single steps; `between` runs before
+    each timed step (outside its events)."""
+    pairs = []
+    for _ in range(steps):
+        if between is not None:
+            between()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        job.step()
+        b.record()
+        pairs.append((a, b))
+    torch.cuda.synchronize()
+    ms = sorted(a.elapsed_time(b) for a, b in pairs)
+    return ms[len(ms) // 2], ms[0]
+
+
 def cpu_baseline(job, W, torch):
     """The oracle, as it stands, on a bounded sample of the same workload."""
     import numpy as np
@@ -318,9 +335,21 @@ def main():
             j = make(name, call)
             _, ev = time_steps(torch, j, 20, 3)
             key = f"{name}:{j.call}"
-            rows[key] = {"ms": round(ev, 5), "GB/s": round(j.bytes / ev / 1e6, 1),
+            med, best = time_each(torch, j, 20)
+            rows[key] = {"ms": round(ev, 5), "median_ms": round(med, 5), "min_ms": round(best, 5),
+                         "GB/s": round(j.bytes / ev / 1e6, 1),
                          "frac_of_peak": round(j.bytes / ev / 1e6 / HBM_PEAK_GBS, 4),
                          "units_per_s": round(j.units / (ev * 1e-3), 1)}
+            if name == "cfg1":
+                # cfg1 fits the caches: also time it with a 1 GiB read-modify-write
+                # between launches, which evicts L2 and the Infinity Cache.
+                thrash = torch.zeros(1 << 28, dtype=torch.float32, device="cuda:0")
+                med, best = time_each(torch, j, 20, between=lambda: thrash.add_(1.0))
+                rows[key + " (caches evicted before each launch)"] = {
+                    "median_ms": round(med, 5), "min_ms": round(best, 5),
+                    "GB/s": round(j.bytes / med / 1e6, 1),
+                    "frac_of_peak": round(j.bytes / med / 1e6 / HBM_PEAK_GBS, 4)}
+                del thrash
             del j
             torch.cuda.empty_cache()
         line["rows"] = rows
