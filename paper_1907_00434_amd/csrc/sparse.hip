@@ -474,17 +474,21 @@ __global__ __launch_bounds__(kScanThreads) void plan_kernel(const BinPlan plan)
 }
 
 // Largest index i in [0, n) with start[i] <= g, for a non-decreasing start[] with
-// start[0] = 0 and g < start[n].
+// start[0] = 0 and g < start[n].  Called by one whole wavefront: its 64 lanes
+// probe 64 evenly spaced entries per round, so that 4,096 entries take two
+// rounds of dependent loads where a binary search by one lane takes twelve.
 __device__ __forceinline__ uint32_t owner_of(const uint32_t *start, uint32_t n, uint32_t g)
 {
-    uint32_t lo = 0, hi = n;
+    const uint32_t lane = threadIdx.x & 63;
+    uint32_t lo = 0, hi = n;                       // the answer is in [lo, hi)
     while (hi - lo > 1) {
-        const uint32_t mid = (lo + hi) >> 1;
-        if (start[mid] <= g) {
-            lo = mid;
-        } else {
-            hi = mid;
-        }
+        const uint32_t step = (hi - lo + 63) / 64;
+        const uint32_t idx = lo + lane * step;
+        // start[lo] <= g always, so lane 0 votes yes; the votes are a prefix of the lanes.
+        const unsigned long long yes = __ballot(idx < hi && start[idx] <= g);
+        const uint32_t last = static_cast<uint32_t>(__popcll(yes)) - 1;
+        lo += last * step;
+        hi = min(lo + step, hi);
     }
     return lo;
 }
@@ -670,7 +674,10 @@ __global__ __launch_bounds__(kPartThreads) void fine_partition_kernel(const BinP
     __shared__ uint32_t s_coarse;
     const uint32_t g = blockIdx.x;
     if (g >= plan.coarse_part_start[plan.n_coarse]) return;   // uniform
-    if (threadIdx.x == 0) s_coarse = owner_of(plan.coarse_part_start, plan.n_coarse, g);
+    if (threadIdx.x < 64) {
+        const uint32_t c = owner_of(plan.coarse_part_start, plan.n_coarse, g);
+        if (threadIdx.x == 0) s_coarse = c;
+    }
     __syncthreads();
     const uint32_t c = s_coarse;
     if (wide_records(plan)) {
@@ -713,7 +720,10 @@ __global__ __launch_bounds__(kAccThreads) void accumulate_kernel(int32_t *__rest
     __shared__ uint32_t s_tile;
     const uint32_t g = blockIdx.x;
     if (g >= plan.chunk_start[plan.n_tiles]) return;          // uniform
-    if (threadIdx.x == 0) s_tile = owner_of(plan.chunk_start, plan.n_tiles, g);
+    if (threadIdx.x < 64) {
+        const uint32_t t = owner_of(plan.chunk_start, plan.n_tiles, g);
+        if (threadIdx.x == 0) s_tile = t;
+    }
     i32x4 *image4 = reinterpret_cast<i32x4 *>(image);
 #pragma unroll
     for (int k = 0; k < kGroupsPerLane; ++k) image4[k * kAccThreads + threadIdx.x] = i32x4{0, 0, 0, 0};
