@@ -246,7 +246,7 @@ def cpu_baseline(job, W, torch):
 def main():
     args = parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU (no sharding, no collectives); "
+        print("bench.py: the library runs on ONE GPU (no sharding, no collectives); "
               "--gpus must be 1", file=sys.stderr)
         sys.exit(2)
 

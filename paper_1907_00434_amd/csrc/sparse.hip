@@ -787,6 +787,10 @@ __global__ __launch_bounds__(kAccThreads) void accumulate_kernel(int32_t *__rest
 #define MLF_DELTA_CHUNK 8
 #endif
 constexpr int kDeltaChunk = MLF_DELTA_CHUNK;   // delta matrices whose loads are in flight together
+#ifndef MLF_DELTA_VPT
+#define MLF_DELTA_VPT 2
+#endif
+constexpr int kDeltaVpt = MLF_DELTA_VPT;       // 128-bit groups per lane and step
 #ifndef MLF_DELTA_MAX_GRID
 #define MLF_DELTA_MAX_GRID 16384
 #endif
@@ -827,30 +831,54 @@ __global__ __launch_bounds__(kThreads) void dense_delta_kernel(const DeltaArgs a
     const unsigned long long stride = static_cast<unsigned long long>(gridDim.x) * kThreads;
     const unsigned long long first = static_cast<unsigned long long>(blockIdx.x) * kThreads + threadIdx.x;
 
-    // 128-bit region: groups of 4 consecutive cells.
+    // 128-bit region: groups of 4 consecutive cells, kDeltaVpt groups per lane
+    // and step, kThreads groups apart.  The counts are loaded together with the
+    // deltas (not after their sum is known), so that the latencies overlap; a
+    // group whose summed delta is zero is not written back.
     const unsigned long long groups = a.n_vec / 4;
-    for (unsigned long long g = first; g < groups; g += stride) {
-        u32x4 sum = {0, 0, 0, 0};
+    u32x4 *counts4 = reinterpret_cast<u32x4 *>(a.counts);
+    for (unsigned long long g0 = first + static_cast<unsigned long long>(blockIdx.x) * kThreads * (kDeltaVpt - 1);
+         g0 < groups; g0 += stride * kDeltaVpt) {
+        u32x4 sum[kDeltaVpt], old[kDeltaVpt];
+        bool on[kDeltaVpt];
+#pragma unroll
+        for (int v = 0; v < kDeltaVpt; ++v) {
+            const unsigned long long g = g0 + static_cast<unsigned long long>(v) * kThreads;
+            on[v] = g < groups;
+            sum[v] = u32x4{0, 0, 0, 0};
+            old[v] = on[v] ? counts4[g] : u32x4{0, 0, 0, 0};
+        }
         for (int k0 = 0; k0 < a.K; k0 += kDeltaChunk) {
-            u32x4 x[kDeltaChunk];
+            u32x4 x[kDeltaChunk][kDeltaVpt];
 #pragma unroll
             for (int c = 0; c < kDeltaChunk; ++c) {
-                x[c] = u32x4{0, 0, 0, 0};
-                if (k0 + c < a.K) {                                  // uniform
-                    x[c] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(a.delta[k0 + c]) + g);
+#pragma unroll
+                for (int v = 0; v < kDeltaVpt; ++v) {
+                    x[c][v] = u32x4{0, 0, 0, 0};
+                    if (k0 + c < a.K && on[v]) {
+                        x[c][v] = __builtin_nontemporal_load(
+                            reinterpret_cast<const u32x4 *>(a.delta[k0 + c]) + g0 +
+                            static_cast<unsigned long long>(v) * kThreads);
+                    }
                 }
             }
 #pragma unroll
-            for (int c = 0; c < kDeltaChunk; ++c) sum += x[c];
-        }
-        if ((sum.x | sum.y | sum.z | sum.w) != 0) {
-            u32x4 *dst = reinterpret_cast<u32x4 *>(a.counts) + g;
-            *dst = *dst + sum;
-            uint32_t col = static_cast<uint32_t>((g * 4) % T);
+            for (int c = 0; c < kDeltaChunk; ++c) {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                add_to_total<LDS_TOTALS>(a, lds_totals, col, sum[j]);
-                col = col + 1 == T ? 0 : col + 1;
+                for (int v = 0; v < kDeltaVpt; ++v) sum[v] += x[c][v];
+            }
+        }
+#pragma unroll
+        for (int v = 0; v < kDeltaVpt; ++v) {
+            if (on[v] && (sum[v].x | sum[v].y | sum[v].z | sum[v].w) != 0) {
+                const unsigned long long g = g0 + static_cast<unsigned long long>(v) * kThreads;
+                counts4[g] = old[v] + sum[v];
+                uint32_t col = static_cast<uint32_t>((g * 4) % T);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    add_to_total<LDS_TOTALS>(a, lds_totals, col, sum[v][j]);
+                    col = col + 1 == T ? 0 : col + 1;
+                }
             }
         }
     }
@@ -1075,7 +1103,7 @@ extern "C" mlf_status mlf_counts_add_dense(int32_t *counts, int32_t *totals, int
     a.K = K;
     a.T = T;
     const unsigned long long work = a.n_vec / 4 > a.n_cells - a.n_vec ? a.n_vec / 4 : a.n_cells - a.n_vec;
-    unsigned long long tiles = (work + kThreads - 1) / kThreads;
+    unsigned long long tiles = (work + kThreads * kDeltaVpt - 1) / (kThreads * kDeltaVpt);
     if (tiles > kDeltaMaxGrid) tiles = kDeltaMaxGrid;
     if (tiles < 1) tiles = 1;
     hipStream_t s = static_cast<hipStream_t>(stream);
