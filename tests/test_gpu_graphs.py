@@ -52,7 +52,7 @@ def test_dense_calls_replay_from_a_graph(name, n):
 
 @pytest.mark.parametrize("use_workspace", [False, True])
 def test_sparse_call_replays_from_a_graph(use_workspace):
-    cfg = W.scaled(W.CONFIGS["cfg5"], V=5003, T=1000, K=3, m=100_000)
+    cfg = W.scaled(W.CONFIGS["cfg5"], V=5003, T=1000, K=3, m=150_000)
     d = W.sparse_inputs(cfg, "cuda", init="random", n_invalid=5)
     counts, totals = d["counts"].clone(), d["totals"].clone()
     rejected = torch.zeros(1, dtype=torch.int32, device="cuda")

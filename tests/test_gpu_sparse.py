@@ -19,6 +19,7 @@ def recipe(**kw):
 @pytest.mark.parametrize("init", ["zeros", "random"])
 def test_scaled_lda_recipe(use_workspace, init):
     cfg = recipe(V=5003, T=1000, K=4, m=300_007)
+    assert mlf.mlf_sparse_workspace_bytes(cfg.V, cfg.T, cfg.K * cfg.m) > 0
     d = W.sparse_inputs(cfg, "cuda", init=init, n_invalid=11)
     counts, totals = run_sparse(cfg, d, use_workspace)
     # totals stay the column sums of counts (they started consistent)
@@ -29,28 +30,29 @@ def test_scaled_lda_recipe(use_workspace, init):
 @pytest.mark.parametrize("use_workspace", [False, True])
 def test_permuted_word_ids(use_workspace):
     cfg = recipe(V=20_011, T=257, K=3, m=200_001)
+    assert mlf.mlf_sparse_workspace_bytes(cfg.V, cfg.T, cfg.K * cfg.m) > 0
     d = W.sparse_inputs(cfg, "cuda", init="random", permute_ids=True)
     run_sparse(cfg, d, use_workspace)
 
 
 @pytest.mark.parametrize("use_workspace", [False, True])
 @pytest.mark.parametrize("V,T,K,m", [(1, 1, 1, 1), (3, 2, 2, 5), (7, 1, 1, 1000), (2, 4099, 3, 777),
-                                     (100, 3, 64, 129), (50_000, 17, 2, 65_536)])
+                                     (100, 3, 64, 129), (50_000, 17, 2, 65_536),
+                                     (50_000, 17, 2, 400_000)])
 def test_odd_shapes(use_workspace, V, T, K, m):
     cfg = recipe(V=V, T=T, K=K, m=m)
     d = W.sparse_inputs(cfg, "cuda", init="random", n_invalid=min(m, 5))
     run_sparse(cfg, d, use_workspace)
 
 
-@pytest.mark.parametrize("V,T,K,m", [(1, 1, 1, 70_000), (3, 2, 2, 40_000), (32_769, 1, 1, 66_000),
-                                     (1, 32_768, 2, 33_000), (7, 9_363, 3, 30_011),
-                                     (4_099, 8, 1, 200_000), (2_100_000, 1, 2, 70_000),
-                                     (16_385, 2_048, 2, 50_000)])
+@pytest.mark.parametrize("V,T,K,m", [(1, 1, 1, 300_000), (3, 2, 2, 150_000), (32_769, 1, 1, 290_000),
+                                     (1, 32_768, 2, 140_000), (7, 9_363, 3, 100_011),
+                                     (4_099, 8, 1, 300_000), (2_100_000, 1, 2, 160_000),
+                                     (16_385, 2_048, 2, 450_000)])
 def test_binned_path_edge_shapes(V, T, K, m):
     """Shapes chosen around the binned path's geometry: one tile shared by
     several workgroups, a matrix that ends just past a tile boundary, many coarse
     ranges, and batches just above the size where the binned path starts."""
-    assert K * m >= 65_536
     cfg = recipe(V=V, T=T, K=K, m=m)
     d = W.sparse_inputs(cfg, "cuda", init="random", n_invalid=7)
     assert mlf.mlf_sparse_workspace_bytes(V, T, K * m) > 0
@@ -61,6 +63,9 @@ def test_shapes_the_binned_path_declines():
     # more than 2^29 cells: no scratch is asked for and the direct path serves
     assert mlf.mlf_sparse_workspace_bytes(70_000, 8_000, 1_000_000) == 0
     assert mlf.mlf_sparse_workspace_bytes(100, 100, 100) == 0        # tiny batch
+    # small batches on a large matrix: the fixed cost per tile would dominate
+    assert mlf.mlf_sparse_workspace_bytes(100_000, 1_000, 1_000_000) == 0
+    assert mlf.mlf_sparse_workspace_bytes(100_000, 1_000, 4_000_000) > 0
     cfg = recipe(V=70_000, T=8_000, K=1, m=100_000)
     d = W.sparse_inputs(cfg, "cuda", init="zeros")
     run_sparse(cfg, d, True)
@@ -107,8 +112,9 @@ def test_wraps_modulo_2_32_and_large_deltas(use_workspace):
 
 @pytest.mark.parametrize("use_workspace", [False, True])
 def test_many_topics_fall_back_to_global_totals(use_workspace):
-    cfg = recipe(V=11, T=20_000, K=2, m=50_000)
+    cfg = recipe(V=11, T=20_000, K=2, m=140_000)
     d = W.sparse_inputs(cfg, "cuda", init="zeros")
+    assert mlf.mlf_sparse_workspace_bytes(cfg.V, cfg.T, cfg.K * cfg.m) > 0
     run_sparse(cfg, d, use_workspace)
 
 
@@ -187,7 +193,8 @@ def test_binned_path_record_formats(big):
     """Deltas in [-1024, 1024) travel as 4-byte records through the scratch, any
     other delta switches the whole call to 8-byte records: both sides of the
     boundary, and extreme values."""
-    cfg = recipe(V=3001, T=500, K=3, m=40_000)
+    cfg = recipe(V=3001, T=500, K=3, m=100_000)
+    assert mlf.mlf_sparse_workspace_bytes(cfg.V, cfg.T, cfg.K * cfg.m) > 0
     d = W.sparse_inputs(cfg, "cuda", init="random", n_invalid=3)
     for k, tr in enumerate(d["triples"]):
         tr[7 + k::997, 2] = big
@@ -199,7 +206,8 @@ def test_binned_path_record_formats(big):
 def test_counts_aligned_to_four_bytes_only(use_workspace):
     """counts (and totals) that are not 16-byte aligned: the merge of the tile
     images falls back to single cells."""
-    cfg = recipe(V=700, T=333, K=2, m=50_000)
+    cfg = recipe(V=700, T=333, K=2, m=140_000)
+    assert mlf.mlf_sparse_workspace_bytes(cfg.V, cfg.T, cfg.K * cfg.m) > 0
     d = W.sparse_inputs(cfg, "cuda", init="random")
     big_c = torch.zeros(cfg.V * cfg.T + 3, dtype=torch.int32, device="cuda")
     big_t = torch.zeros(cfg.T + 3, dtype=torch.int32, device="cuda")
