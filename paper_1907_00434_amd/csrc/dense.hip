@@ -558,14 +558,15 @@ mlf_status dispatch(DenseArgs &a, mlf_dtype dtype, hipStream_t stream, double *n
                     size_t capacity = 0)
 {
     // State that is too large to survive in the Infinity Cache until the next
-    // call is streamed through; smaller state is left cacheable.
+    // call is streamed through; smaller state is left cacheable.  The output of
+    // a plain aggregate is never read back by this library: always streamed.
     long long footprint = 0;
     if (a.model != nullptr) footprint += 4 * a.n;
     if (a.momentum != nullptr) footprint += 4 * a.n;
     if (a.out != nullptr) footprint += 4 * a.n;
     constexpr int kS = MLF_STATE_POLICY >= 2 ? MLF_STATE_POLICY - 1 : 3;
     const bool streaming = MLF_STATE_POLICY >= 2 ||
-                           (MLF_STATE_POLICY == 0 && footprint > kInfinityCacheBytes);
+                           (MLF_STATE_POLICY == 0 && (OP == kAggregate || footprint > kInfinityCacheBytes));
     if (dtype == MLF_F32) {
         return streaming ? dispatch_state<F32, OP, kS, NORMS>(a, stream, norms_out, capacity)
                          : dispatch_state<F32, OP, 0, NORMS>(a, stream, norms_out, capacity);
