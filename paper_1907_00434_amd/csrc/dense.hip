@@ -344,6 +344,30 @@ struct Tile {
     }
 };
 
+// Workgroups are handed to the 8 XCDs (each with its own L2) in turn.  With
+// RUN > 0 every XCD takes runs of RUN consecutive tiles instead of every eighth
+// tile, so that the lines an L2 writes back lie together; the last, incomplete
+// block of 8 * RUN workgroups keeps the plain numbering, which keeps the map
+// one to one.  Used where model and momentum go through the caches (+5 % there;
+// no gain, or a loss, where they are streamed).
+#ifndef MLF_XCD_RUN
+#define MLF_XCD_RUN 512
+#endif
+
+template <unsigned RUN>
+__device__ __forceinline__ long long xcd_tile(unsigned block, unsigned tiles)
+{
+    if constexpr (RUN == 0) {
+        return block;
+    } else {
+        constexpr unsigned kBlock = 8 * RUN;
+        const unsigned first = block / kBlock * kBlock;
+        if (first + kBlock > tiles) return block;
+        const unsigned r = block - first;
+        return first + (r % 8) * RUN + r / 8;
+    }
+}
+
 // Workgroups [0, tiles_vec) take one tile each of the 128-bit region
 // [0, n_vec); the remaining workgroups stride over the element-wise region
 // [n_vec, n): the ragged tail, or everything when a pointer of the call is not
@@ -358,7 +382,8 @@ __global__ __launch_bounds__(THREADS) void dense_kernel(const DenseArgs a)
     double sums[2] = {0.0, 0.0};
     if (blockIdx.x < a.tiles_vec) {
         const long long groups = a.n_vec / WV;
-        const long long base = blockIdx.x * kTile;
+        constexpr unsigned kRun = (STREAM == 0 && OP != kAggregate) ? MLF_XCD_RUN : 0;
+        const long long base = xcd_tile<kRun>(blockIdx.x, a.tiles_vec) * kTile;
         if (base + kTile <= groups) {
             Tile<IN, WV, OP, HAS_H, STREAM, NORMS, THREADS, VPT, CH, true>(a, 0, base + threadIdx.x, groups).run(sums);
         } else {
@@ -384,26 +409,34 @@ __global__ __launch_bounds__(THREADS) void dense_kernel(const DenseArgs a)
     }
 }
 
-// Sums the per-workgroup partial sums in a fixed order (lane i takes partials
-// i, i + 1024, ... in turn, then a tree over the lanes), so that the norms of
-// a call are reproducible bit for bit for a given launch shape.
+// Sums pairs of partial sums in a fixed order, so that the norms of a call are
+// reproducible bit for bit for a given launch shape.  Workgroup b takes the
+// pairs [b * slice, (b + 1) * slice) (cut at n_partials): lane i adds the
+// pairs i, i + 1024, ... of the slice in turn, then a tree over the lanes; the
+// result goes to out[2b] (and out[2b + 1] if n_out > 1).  A long list is
+// reduced in two launches: kFinishSlices slices, then their sums.
 constexpr int kFinishThreads = 1024;
+constexpr unsigned kFinishSlices = 64;
+constexpr unsigned kFinishTwoStageMin = 16384;   // pairs; below this one workgroup does it all
 
 __global__ __launch_bounds__(kFinishThreads) void norms_finish_kernel(const double *partials,
                                                                       unsigned n_partials,
-                                                                      double *out, int n_out)
+                                                                      unsigned slice, double *out,
+                                                                      int n_out)
 {
     __shared__ double tree[2][kFinishThreads];
     typedef double f64x2 __attribute__((ext_vector_type(2)));
     const f64x2 *pairs = reinterpret_cast<const f64x2 *>(partials);
+    const unsigned begin = min(blockIdx.x * slice, n_partials);
+    const unsigned end = min(begin + slice, n_partials);
     double s0 = 0.0, s1 = 0.0;
     // Eight loads in flight per lane; the additions keep their order.
-    for (unsigned j0 = threadIdx.x; j0 < n_partials; j0 += kFinishThreads * 8) {
+    for (unsigned j0 = begin + threadIdx.x; j0 < end; j0 += kFinishThreads * 8) {
         f64x2 v[8];
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
             const unsigned j = j0 + u * kFinishThreads;
-            v[u] = j < n_partials ? pairs[j] : f64x2{0.0, 0.0};
+            v[u] = j < end ? pairs[j] : f64x2{0.0, 0.0};
         }
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
@@ -422,9 +455,30 @@ __global__ __launch_bounds__(kFinishThreads) void norms_finish_kernel(const doub
         __syncthreads();
     }
     if (threadIdx.x == 0) {
-        out[0] = tree[0][0];
-        if (n_out > 1) out[1] = tree[1][0];
+        out[2 * static_cast<size_t>(blockIdx.x)] = tree[0][0];
+        if (n_out > 1) out[2 * static_cast<size_t>(blockIdx.x) + 1] = tree[1][0];
     }
+}
+
+// Launches the reduction of `n_partials` pairs at `partials` into out[0..n_out).
+// The kFinishSlices pairs after the capacity of the list are the scratch of the
+// two-stage form.
+bool finish_norms(double *partials, unsigned n_partials, size_t capacity, double *out, int n_out,
+                  hipStream_t stream)
+{
+    if (n_partials >= kFinishTwoStageMin) {
+        double *slices = partials + 2 * capacity;
+        const unsigned slice = (n_partials + kFinishSlices - 1) / kFinishSlices;
+        norms_finish_kernel<<<dim3(kFinishSlices), dim3(kFinishThreads), 0, stream>>>(
+            partials, n_partials, slice, slices, 2);
+        if (hipGetLastError() != hipSuccess) return false;
+        norms_finish_kernel<<<dim3(1), dim3(kFinishThreads), 0, stream>>>(
+            slices, kFinishSlices, kFinishSlices, out, n_out);
+    } else {
+        norms_finish_kernel<<<dim3(1), dim3(kFinishThreads), 0, stream>>>(
+            partials, n_partials, n_partials, out, n_out);
+    }
+    return hipGetLastError() == hipSuccess;
 }
 
 // Exact server-replica divergence (Sec. 3.3 / 5.3: bounded consistency keeps
@@ -519,9 +573,9 @@ mlf_status launch_shape(DenseArgs &a, hipStream_t stream, double *norms_out,
         if (hipGetLastError() != hipSuccess) return MLF_EHIP;
     }
     if constexpr (NORMS) {
-        norms_finish_kernel<<<dim3(1), dim3(kFinishThreads), 0, stream>>>(
-            a.partials, grid, norms_out, OP == kAggregate ? 1 : 2);
-        if (hipGetLastError() != hipSuccess) return MLF_EHIP;
+        if (!finish_norms(a.partials, grid, partials_capacity, norms_out, OP == kAggregate ? 1 : 2, stream)) {
+            return MLF_EHIP;
+        }
     }
     return MLF_OK;
 }
@@ -736,7 +790,7 @@ static size_t norms_partials_capacity(long long n)
 extern "C" size_t mlf_norms_workspace_bytes(int64_t n)
 {
     if (n < 0) return 0;
-    return norms_partials_capacity(n) * 2 * sizeof(double);
+    return (norms_partials_capacity(n) + kFinishSlices) * 2 * sizeof(double);
 }
 
 extern "C" mlf_status mlf_aggregate_norm(const void *const *update_ptrs, int K, int64_t n,
@@ -816,8 +870,7 @@ extern "C" mlf_status mlf_divergence(const float *w_server, const float *w_repli
                                                          static_cast<unsigned>(tiles_v), partials);
         if (hipGetLastError() != hipSuccess) return MLF_EHIP;
     }
-    norms_finish_kernel<<<dim3(1), dim3(kFinishThreads), 0, s>>>(partials, grid, dist_sq, 1);
-    return hipGetLastError() == hipSuccess ? MLF_OK : MLF_EHIP;
+    return finish_norms(partials, grid, norms_partials_capacity(n), dist_sq, 1, s) ? MLF_OK : MLF_EHIP;
 }
 
 extern "C" const char *mlf_status_string(mlf_status status)

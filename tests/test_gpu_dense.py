@@ -49,6 +49,18 @@ def test_config_recipes_over_many_tiles(call, name):
     run_dense(call, d, want_out=True)
 
 
+@pytest.mark.parametrize("call", ["apply_ordered", "aggregate_apply"])
+@pytest.mark.parametrize("dtype,n", [("f32", 512 * (2 * 4096 + 37) + 3),
+                                     ("bf16", 2048 * (4096 + 5) + 9)])
+def test_tile_numbering_over_whole_and_partial_blocks(call, dtype, n):
+    """Cache-resident state: workgroups take tiles in runs per XCD, block by
+    block of 4,096 tiles, the last partial block in plain order.  Sizes with whole
+    blocks, a partial block and a ragged tail; every element must be visited once."""
+    cfg = recipe("cfg2", n=n, K=2, dtype=dtype)
+    d = W.dense_inputs(cfg, "cuda", momentum_init="random")
+    run_dense(call, d, want_out=True)
+
+
 @pytest.mark.parametrize("call", CALLS)
 def test_dropped_updates_and_null_pointers(call):
     cfg = recipe("cfg2", n=5000, K=8)
