@@ -70,6 +70,18 @@ constexpr uint32_t kPartTile = kPartThreads * kPartItems;      // records per st
 constexpr uint32_t kCursorStride = MLF_CURSOR_STRIDE;
 constexpr int kAccThreads = MLF_ACC_THREADS;     // lanes of an accumulate workgroup
 constexpr uint32_t kAccChunk = 1u << MLF_ACC_CHUNK_BITS;   // records per accumulate work item
+#ifndef MLF_SCAN_UNROLL
+#define MLF_SCAN_UNROLL 2
+#endif
+#ifndef MLF_SCAN_BLOCK
+#define MLF_SCAN_BLOCK 1024
+#endif
+#ifndef MLF_SCAN_WGS
+#define MLF_SCAN_WGS 512
+#endif
+constexpr int kScanBlock = MLF_SCAN_BLOCK;                    // lanes of a first-pass workgroup
+constexpr int kScanWorkgroups = MLF_SCAN_WGS;                 // first-pass workgroups of a call, about
+constexpr int kScanUnroll = MLF_SCAN_UNROLL;                  // triples per lane and step of the first pass
 constexpr int kScanThreads = 1024;
 constexpr int kScanItems = kMaxTiles / kScanThreads;           // 16
 // The binned path has a fixed cost (six launches, one accumulate workgroup per
@@ -251,13 +263,13 @@ __device__ __forceinline__ bool load_triple(const int32_t *tr, long long r, int 
            static_cast<unsigned>(topic) < static_cast<unsigned>(T);
 }
 
-// First pass over the triples; blockIdx.y = worker buffer, blockIdx.x strides
-// over that buffer.  BINNED = false: the direct path (counts[] updated here).
+// First pass over the triples; blockIdx.y = worker buffer, blockIdx.x = share
+// of that buffer.  BINNED = false: the direct path (counts[] updated here).
 // BINNED = true: only the per-tile histogram is built.  Both keep the totals in
 // LDS and count the rejected triples.
 // Dynamic LDS: [T totals if LDS_TOTALS][n_tiles histogram if BINNED].
 template <bool BINNED, bool LDS_TOTALS>
-__global__ __launch_bounds__(kThreads) void scan_triples_kernel(const SparseArgs a,
+__global__ __launch_bounds__(kScanBlock) void scan_triples_kernel(const SparseArgs a,
                                                                 const BinPlan plan)
 {
     extern __shared__ int32_t lds[];
@@ -266,38 +278,56 @@ __global__ __launch_bounds__(kThreads) void scan_triples_kernel(const SparseArgs
     int32_t *lds_totals = lds;
     uint32_t *lds_hist = reinterpret_cast<uint32_t *>(lds + (LDS_TOTALS ? T : 0));
     if constexpr (LDS_TOTALS) {
-        for (int t = threadIdx.x; t < T; t += kThreads) lds_totals[t] = 0;
+        for (int t = threadIdx.x; t < T; t += kScanBlock) lds_totals[t] = 0;
     }
     if constexpr (BINNED) {
-        for (uint32_t b = threadIdx.x; b < plan.n_tiles; b += kThreads) lds_hist[b] = 0;
+        for (uint32_t b = threadIdx.x; b < plan.n_tiles; b += kScanBlock) lds_hist[b] = 0;
     }
     if constexpr (LDS_TOTALS || BINNED) __syncthreads();
 
     const int k = blockIdx.y;
     const int32_t *tr = a.triples[k];
     const long long m = a.n_triples[k];
-    const long long stride = static_cast<long long>(gridDim.x) * kThreads;
+    // Each workgroup streams one contiguous share of the buffer (rather than
+    // striding over it with the others), so that at any moment the workgroups
+    // of a launch read from places spread over all the buffers.
+    constexpr long long kStep = static_cast<long long>(kScanBlock) * kScanUnroll;
+    const long long share = ((m + gridDim.x - 1) / gridDim.x + kStep - 1) / kStep * kStep;
+    const long long begin = min(static_cast<long long>(blockIdx.x) * share, m);
+    const long long end = min(begin + share, m);
     int n_bad = 0;
     bool wide = false;
-    for (long long r = static_cast<long long>(blockIdx.x) * kThreads + threadIdx.x; r < m;
-         r += stride) {
-        int word, topic, delta;
-        if (!load_triple(tr, r, a.V, T, word, topic, delta)) {
-            ++n_bad;
-            continue;
+    // kScanUnroll triples per lane and step, all loaded before the first is used.
+    for (long long r0 = begin + threadIdx.x; r0 < end; r0 += kStep) {
+        int word[kScanUnroll], topic[kScanUnroll], delta[kScanUnroll];
+        bool there[kScanUnroll], good[kScanUnroll];
+#pragma unroll
+        for (int u = 0; u < kScanUnroll; ++u) {
+            const long long r = r0 + u * kScanBlock;
+            there[u] = r < end;
+            word[u] = topic[u] = delta[u] = 0;
+            good[u] = there[u] && load_triple(tr, r, a.V, T, word[u], topic[u], delta[u]);
         }
-        const long long cell = static_cast<long long>(word) * T + topic;
-        if constexpr (BINNED) {
-            wide = wide || delta < -kSmallDeltaLimit || delta >= kSmallDeltaLimit;
-            wave_count(lds_hist, static_cast<uint32_t>(cell) >> kTileBits);
-        } else {
-            add_relaxed(a.counts + cell, delta);
-        }
-        if (want_totals) {
-            if constexpr (LDS_TOTALS) {
-                lds_add(&lds_totals[topic], delta);
+#pragma unroll
+        for (int u = 0; u < kScanUnroll; ++u) {
+            if (!there[u]) continue;
+            if (!good[u]) {
+                ++n_bad;
+                continue;
+            }
+            const long long cell = static_cast<long long>(word[u]) * T + topic[u];
+            if constexpr (BINNED) {
+                wide = wide || delta[u] < -kSmallDeltaLimit || delta[u] >= kSmallDeltaLimit;
+                wave_count(lds_hist, static_cast<uint32_t>(cell) >> kTileBits);
             } else {
-                add_relaxed(a.totals + topic, delta);
+                add_relaxed(a.counts + cell, delta[u]);
+            }
+            if (want_totals) {
+                if constexpr (LDS_TOTALS) {
+                    lds_add(&lds_totals[topic[u]], delta[u]);
+                } else {
+                    add_relaxed(a.totals + topic[u], delta[u]);
+                }
             }
         }
     }
@@ -305,14 +335,14 @@ __global__ __launch_bounds__(kThreads) void scan_triples_kernel(const SparseArgs
     if constexpr (LDS_TOTALS || BINNED) __syncthreads();
     if constexpr (LDS_TOTALS) {
         if (want_totals) {
-            for (int t = threadIdx.x; t < T; t += kThreads) {
+            for (int t = threadIdx.x; t < T; t += kScanBlock) {
                 const int32_t v = lds_totals[t];
                 if (v != 0) add_relaxed(a.totals + t, v);
             }
         }
     }
     if constexpr (BINNED) {
-        for (uint32_t b = threadIdx.x; b < plan.n_tiles; b += kThreads) {
+        for (uint32_t b = threadIdx.x; b < plan.n_tiles; b += kScanBlock) {
             const uint32_t v = lds_hist[b];
             if (v != 0) fetch_add_relaxed(plan.hist + b, v);
         }
@@ -1026,8 +1056,8 @@ extern "C" mlf_status mlf_sparse_scatter_add(int32_t *counts, int32_t *totals, i
     // The first pass over the triples: enough workgroups to fill the chip, few
     // enough that their merges of private totals / histograms stay small next to
     // the streamed triples.
-    long long per_buffer = (longest + kThreads * 16 - 1) / (kThreads * 16);
-    const long long cap = (2048 + used - 1) / used;
+    long long per_buffer = (longest + kScanBlock * 16 - 1) / (kScanBlock * 16);
+    const long long cap = (kScanWorkgroups + used - 1) / used;
     if (per_buffer > cap) per_buffer = cap;
     if (per_buffer < 1) per_buffer = 1;
     const dim3 scan_grid(static_cast<unsigned>(per_buffer), static_cast<unsigned>(used));
@@ -1040,9 +1070,9 @@ extern "C" mlf_status mlf_sparse_scatter_add(int32_t *counts, int32_t *totals, i
                         reinterpret_cast<uintptr_t>(workspace) % 256 == 0;
     if (!binned) {
         if (lds_totals) {
-            scan_triples_kernel<false, true><<<scan_grid, dim3(kThreads), totals_lds, s>>>(a, plan);
+            scan_triples_kernel<false, true><<<scan_grid, dim3(kScanBlock), totals_lds, s>>>(a, plan);
         } else {
-            scan_triples_kernel<false, false><<<scan_grid, dim3(kThreads), 0, s>>>(a, plan);
+            scan_triples_kernel<false, false><<<scan_grid, dim3(kScanBlock), 0, s>>>(a, plan);
         }
         return launched() ? MLF_OK : MLF_EHIP;
     }
@@ -1058,9 +1088,9 @@ extern "C" mlf_status mlf_sparse_scatter_add(int32_t *counts, int32_t *totals, i
         totals_lds = 0;
     }
     if (lds_totals) {
-        scan_triples_kernel<true, true><<<scan_grid, dim3(kThreads), totals_lds + hist_lds, s>>>(a, plan);
+        scan_triples_kernel<true, true><<<scan_grid, dim3(kScanBlock), totals_lds + hist_lds, s>>>(a, plan);
     } else {
-        scan_triples_kernel<true, false><<<scan_grid, dim3(kThreads), hist_lds, s>>>(a, plan);
+        scan_triples_kernel<true, false><<<scan_grid, dim3(kScanBlock), hist_lds, s>>>(a, plan);
     }
     if (!launched()) return MLF_EHIP;
     plan_kernel<<<dim3(1), dim3(kScanThreads), 0, s>>>(plan);
