@@ -29,11 +29,11 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
 # 1.000, the factors a plain 1 GiB copy calibrates), taken with the kernels as
 # they are in this tree (summary kept under profiles/).  cfg5 = whole call.
 MEASURED_TRAFFIC_BYTES = {
-    "cfg1": 25.2e6,
-    "cfg2": 2044.7e6,
-    "cfg3": 8798.6e6,
-    "cfg4": 4427.5e6,
-    "cfg5": 2848.4e6,
+    "cfg1": 25.3e6,
+    "cfg2": 2044.6e6,
+    "cfg3": 8798.4e6,
+    "cfg4": 4427.4e6,
+    "cfg5": 2824.0e6,
 }
 
 

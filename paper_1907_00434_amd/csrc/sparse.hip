@@ -825,8 +825,12 @@ constexpr int kDeltaChunk = MLF_DELTA_CHUNK;   // delta matrices whose loads are
 #define MLF_DELTA_VPT 2
 #endif
 constexpr int kDeltaVpt = MLF_DELTA_VPT;       // 128-bit groups per lane and step
+#ifndef MLF_DELTA_THREADS
+#define MLF_DELTA_THREADS 1024
+#endif
+constexpr int kDeltaThreads = MLF_DELTA_THREADS;   // lanes of a workgroup
 #ifndef MLF_DELTA_MAX_GRID
-#define MLF_DELTA_MAX_GRID 16384
+#define MLF_DELTA_MAX_GRID 2048
 #endif
 constexpr unsigned kDeltaMaxGrid = MLF_DELTA_MAX_GRID;
 
@@ -853,31 +857,31 @@ __device__ __forceinline__ void add_to_total(const DeltaArgs &a, int32_t *lds_to
 }
 
 template <bool LDS_TOTALS>
-__global__ __launch_bounds__(kThreads) void dense_delta_kernel(const DeltaArgs a)
+__global__ __launch_bounds__(kDeltaThreads) void dense_delta_kernel(const DeltaArgs a)
 {
     typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
     extern __shared__ int32_t lds_totals[];
     const uint32_t T = static_cast<uint32_t>(a.T);
     if constexpr (LDS_TOTALS) {
-        for (uint32_t t = threadIdx.x; t < T; t += kThreads) lds_totals[t] = 0;
+        for (uint32_t t = threadIdx.x; t < T; t += kDeltaThreads) lds_totals[t] = 0;
         __syncthreads();
     }
-    const unsigned long long stride = static_cast<unsigned long long>(gridDim.x) * kThreads;
-    const unsigned long long first = static_cast<unsigned long long>(blockIdx.x) * kThreads + threadIdx.x;
+    const unsigned long long stride = static_cast<unsigned long long>(gridDim.x) * kDeltaThreads;
+    const unsigned long long first = static_cast<unsigned long long>(blockIdx.x) * kDeltaThreads + threadIdx.x;
 
     // 128-bit region: groups of 4 consecutive cells, kDeltaVpt groups per lane
-    // and step, kThreads groups apart.  The counts are loaded together with the
+    // and step, kDeltaThreads groups apart.  The counts are loaded together with the
     // deltas (not after their sum is known), so that the latencies overlap; a
     // group whose summed delta is zero is not written back.
     const unsigned long long groups = a.n_vec / 4;
     u32x4 *counts4 = reinterpret_cast<u32x4 *>(a.counts);
-    for (unsigned long long g0 = first + static_cast<unsigned long long>(blockIdx.x) * kThreads * (kDeltaVpt - 1);
+    for (unsigned long long g0 = first + static_cast<unsigned long long>(blockIdx.x) * kDeltaThreads * (kDeltaVpt - 1);
          g0 < groups; g0 += stride * kDeltaVpt) {
         u32x4 sum[kDeltaVpt], old[kDeltaVpt];
         bool on[kDeltaVpt];
 #pragma unroll
         for (int v = 0; v < kDeltaVpt; ++v) {
-            const unsigned long long g = g0 + static_cast<unsigned long long>(v) * kThreads;
+            const unsigned long long g = g0 + static_cast<unsigned long long>(v) * kDeltaThreads;
             on[v] = g < groups;
             sum[v] = u32x4{0, 0, 0, 0};
             old[v] = on[v] ? counts4[g] : u32x4{0, 0, 0, 0};
@@ -892,7 +896,7 @@ __global__ __launch_bounds__(kThreads) void dense_delta_kernel(const DeltaArgs a
                     if (k0 + c < a.K && on[v]) {
                         x[c][v] = __builtin_nontemporal_load(
                             reinterpret_cast<const u32x4 *>(a.delta[k0 + c]) + g0 +
-                            static_cast<unsigned long long>(v) * kThreads);
+                            static_cast<unsigned long long>(v) * kDeltaThreads);
                     }
                 }
             }
@@ -905,7 +909,7 @@ __global__ __launch_bounds__(kThreads) void dense_delta_kernel(const DeltaArgs a
 #pragma unroll
         for (int v = 0; v < kDeltaVpt; ++v) {
             if (on[v] && (sum[v].x | sum[v].y | sum[v].z | sum[v].w) != 0) {
-                const unsigned long long g = g0 + static_cast<unsigned long long>(v) * kThreads;
+                const unsigned long long g = g0 + static_cast<unsigned long long>(v) * kDeltaThreads;
                 counts4[g] = old[v] + sum[v];
                 uint32_t col = static_cast<uint32_t>((g * 4) % T);
 #pragma unroll
@@ -931,7 +935,7 @@ __global__ __launch_bounds__(kThreads) void dense_delta_kernel(const DeltaArgs a
     if constexpr (LDS_TOTALS) {
         __syncthreads();
         if (a.totals != nullptr) {
-            for (uint32_t t = threadIdx.x; t < T; t += kThreads) {
+            for (uint32_t t = threadIdx.x; t < T; t += kDeltaThreads) {
                 const int32_t v = lds_totals[t];
                 if (v != 0) add_relaxed(a.totals + t, v);
             }
@@ -1135,15 +1139,15 @@ extern "C" mlf_status mlf_counts_add_dense(int32_t *counts, int32_t *totals, int
     a.K = K;
     a.T = T;
     const unsigned long long work = a.n_vec / 4 > a.n_cells - a.n_vec ? a.n_vec / 4 : a.n_cells - a.n_vec;
-    unsigned long long tiles = (work + kThreads * kDeltaVpt - 1) / (kThreads * kDeltaVpt);
+    unsigned long long tiles = (work + kDeltaThreads * kDeltaVpt - 1) / (kDeltaThreads * kDeltaVpt);
     if (tiles > kDeltaMaxGrid) tiles = kDeltaMaxGrid;
     if (tiles < 1) tiles = 1;
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (totals != nullptr && T <= kMaxLdsTopics) {
-        dense_delta_kernel<true><<<dim3(static_cast<unsigned>(tiles)), dim3(kThreads),
+        dense_delta_kernel<true><<<dim3(static_cast<unsigned>(tiles)), dim3(kDeltaThreads),
                                    static_cast<size_t>(T) * sizeof(int32_t), s>>>(a);
     } else {
-        dense_delta_kernel<false><<<dim3(static_cast<unsigned>(tiles)), dim3(kThreads), 0, s>>>(a);
+        dense_delta_kernel<false><<<dim3(static_cast<unsigned>(tiles)), dim3(kDeltaThreads), 0, s>>>(a);
     }
     return launched() ? MLF_OK : MLF_EHIP;
 }
