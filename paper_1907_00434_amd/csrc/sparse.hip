@@ -212,6 +212,14 @@ __device__ __forceinline__ uint32_t lanes_below(unsigned long long mask)
                                      __builtin_amdgcn_mbcnt_lo(static_cast<uint32_t>(mask), 0u));
 }
 
+// The value of lane `lane` (the same for all lanes of the wavefront) in every
+// lane: a register read, where a shuffle would go through the LDS pipeline.
+__device__ __forceinline__ uint32_t broadcast(uint32_t v, int lane)
+{
+    return static_cast<uint32_t>(
+        __builtin_amdgcn_readlane(static_cast<int>(v), __builtin_amdgcn_readfirstlane(lane)));
+}
+
 // counter[bin] += 1 for every live lane, returning to each the value it would
 // have seen had the lanes gone one by one (its rank in the bin).  Skewed data
 // puts most lanes of a wavefront into one bin, and LDS atomics on one address
@@ -223,14 +231,14 @@ __device__ __forceinline__ uint32_t wave_rank(uint32_t *counter, uint32_t bin, b
     const unsigned long long live_mask = __ballot(live);
     if (live_mask == 0) return 0;                                   // uniform
     const int leader = __ffsll(static_cast<long long>(live_mask)) - 1;
-    const uint32_t lead_bin = __shfl(bin, leader, 64);
+    const uint32_t lead_bin = broadcast(bin, leader);
     const bool grouped = live && bin == lead_bin;
     const unsigned long long group = __ballot(grouped);
     uint32_t base = 0;
     if (static_cast<int>(threadIdx.x & 63) == leader) {
         base = lds_fetch_add(&counter[lead_bin], static_cast<uint32_t>(__popcll(group)));
     }
-    base = __shfl(base, leader, 64);
+    base = broadcast(base, leader);
     if (grouped) return base + lanes_below(group);
     return live ? lds_fetch_add(&counter[bin], 1u) : 0u;
 }
@@ -241,7 +249,7 @@ __device__ __forceinline__ void wave_count(uint32_t *counter, uint32_t bin)
 {
     const unsigned long long active = __ballot(true);
     const int leader = __ffsll(static_cast<long long>(active)) - 1;
-    const uint32_t lead_bin = __shfl(bin, leader, 64);
+    const uint32_t lead_bin = broadcast(bin, leader);
     const bool grouped = bin == lead_bin;
     const unsigned long long group = __ballot(grouped);
     if (static_cast<int>(threadIdx.x & 63) == leader) {
@@ -724,23 +732,52 @@ __global__ __launch_bounds__(kPartThreads) void fine_partition_kernel(const BinP
 // Accumulate: workgroup g takes up to kAccChunk records of one tile, sums them
 // into a private LDS image of the tile and merges the image into counts[].
 typedef int32_t i32x4 __attribute__((ext_vector_type(4)));
-constexpr int kAccUnroll = 8;                    // record loads in flight per lane
+#ifndef MLF_ACC_UNROLL
+#define MLF_ACC_UNROLL 4
+#endif
+constexpr int kAccUnroll = MLF_ACC_UNROLL;       // 128-bit record loads in flight per lane
 
-// Adds the records [begin, end) of one tile into its LDS image.
+// Adds the records [begin, end) of one tile into its LDS image.  The records
+// are read with 128-bit loads (4 narrow or 2 wide records each), kAccUnroll of
+// them in flight per lane; the few records before the first and after the last
+// aligned group go one by one.
 template <bool WIDE>
 __device__ __forceinline__ void accumulate_records(int32_t *image, const void *__restrict__ sorted,
                                                    uint32_t begin, uint32_t end)
 {
-    for (uint32_t r0 = begin + threadIdx.x; r0 < end; r0 += kAccThreads * kAccUnroll) {
-        Record rec[kAccUnroll];
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    constexpr uint32_t kPer = WIDE ? 2 : 4;
+    const uint32_t first = min((begin + kPer - 1) / kPer * kPer, end);
+    const uint32_t last = max(first, end / kPer * kPer);
+    auto add_one = [&](uint32_t r) {
+        const Record rec = load_sorted<WIDE>(sorted, r);
+        lds_add(&image[rec.cell], rec.delta);
+    };
+    if (threadIdx.x < first - begin) add_one(begin + threadIdx.x);
+    if (threadIdx.x < end - last) add_one(last + threadIdx.x);
+
+    const u32x4 *groups = static_cast<const u32x4 *>(sorted);
+    const uint32_t g_end = last / kPer;
+    for (uint32_t g0 = first / kPer + threadIdx.x; g0 < g_end; g0 += kAccThreads * kAccUnroll) {
+        u32x4 x[kAccUnroll];
 #pragma unroll
         for (int u = 0; u < kAccUnroll; ++u) {
-            const uint32_t r = r0 + u * kAccThreads;
-            rec[u] = r < end ? load_sorted<WIDE>(sorted, r) : Record{0u, 0};
+            const uint32_t g = g0 + u * kAccThreads;
+            x[u] = g < g_end ? groups[g] : u32x4{0, 0, 0, 0};
         }
 #pragma unroll
         for (int u = 0; u < kAccUnroll; ++u) {
-            if (r0 + u * kAccThreads < end) lds_add(&image[rec[u].cell], rec[u].delta);
+            if (g0 + u * kAccThreads >= g_end) continue;
+            if constexpr (WIDE) {
+                lds_add(&image[x[u].x & (kTileCells - 1)], static_cast<int32_t>(x[u].y));
+                lds_add(&image[x[u].z & (kTileCells - 1)], static_cast<int32_t>(x[u].w));
+            } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const uint32_t v = x[u][j];
+                    lds_add(&image[v & (kTileCells - 1)], static_cast<int32_t>(v) >> kTileBits);
+                }
+            }
         }
     }
 }
