@@ -609,8 +609,7 @@ __device__ __forceinline__ void partition_step(PartitionLds &s, const Record (&r
 // Valid triples become records: those of hot tiles go to their final place in
 // plan.sorted, the others to plan.tmp, grouped by coarse range.
 struct HotLds {
-    uint32_t bits[kHotWords];
-    uint16_t before[kHotWords];
+    uint2 word[kHotWords];      // x = bitmap word, y = hot tiles before it: one 64-bit read per lookup
 };
 
 template <bool WIDE>
@@ -634,8 +633,7 @@ __device__ __forceinline__ void coarse_partition_body(PartitionLds &s, HotLds &h
     // The hot-tile bitmap and the digit counters, while the triples are in flight.
     static_assert(kHotWords <= kPartThreads && kMaxCoarse <= kPartThreads, "one word per lane");
     if (threadIdx.x < kHotWords) {
-        hot.bits[threadIdx.x] = plan.hot_bits[threadIdx.x];
-        hot.before[threadIdx.x] = static_cast<uint16_t>(plan.hot_before[threadIdx.x]);
+        hot.word[threadIdx.x] = make_uint2(plan.hot_bits[threadIdx.x], plan.hot_before[threadIdx.x]);
     }
     if (threadIdx.x < kMaxCoarse) s.count[threadIdx.x] = 0;
     __syncthreads();
@@ -645,10 +643,10 @@ __device__ __forceinline__ void coarse_partition_body(PartitionLds &s, HotLds &h
         s, rec, live,
         [=](uint32_t cell) {
             const uint32_t tile = cell >> kTileBits;
-            const uint32_t word = h->bits[tile >> 5];
+            const uint2 entry = h->word[tile >> 5];
             const uint32_t bit = tile & 31;
-            if ((word >> bit) & 1u) {
-                return n_coarse + h->before[tile >> 5] + static_cast<uint32_t>(__popc(word & ((1u << bit) - 1u)));
+            if ((entry.x >> bit) & 1u) {
+                return n_coarse + entry.y + static_cast<uint32_t>(__popc(entry.x & ((1u << bit) - 1u)));
             }
             return tile >> kFineBits;
         },
