@@ -350,6 +350,31 @@ def main():
                     "GB/s": round(j.bytes / med / 1e6, 1),
                     "frac_of_peak": round(j.bytes / med / 1e6 / HBM_PEAK_GBS, 4)}
                 del thrash
+                # Back-to-back calls from Python are launch-bound at this size;
+                # recorded into a HIP graph (20 calls per replay) they are not.
+                side = torch.cuda.Stream()
+                side.wait_stream(torch.cuda.current_stream())
+                with torch.cuda.stream(side):
+                    j.step()
+                torch.cuda.current_stream().wait_stream(side)
+                torch.cuda.synchronize()
+                graph = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(graph):
+                    for _ in range(20):
+                        j.step()
+                graph.replay()
+                torch.cuda.synchronize()
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record()
+                for _ in range(10):
+                    graph.replay()
+                b.record()
+                torch.cuda.synchronize()
+                per_call = a.elapsed_time(b) / 200
+                rows[key + " (HIP graph of 20 calls)"] = {
+                    "ms": round(per_call, 5), "GB/s": round(j.bytes / per_call / 1e6, 1),
+                    "frac_of_peak": round(j.bytes / per_call / 1e6 / HBM_PEAK_GBS, 4)}
+                del graph
             del j
             torch.cuda.empty_cache()
         line["rows"] = rows
