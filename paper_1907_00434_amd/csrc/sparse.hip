@@ -44,7 +44,7 @@ constexpr int kMaxLdsTopics = 16384;     // totals privatised in LDS up to 64 Ki
 #define MLF_ACC_THREADS 1024
 #endif
 #ifndef MLF_ACC_CHUNK_BITS
-#define MLF_ACC_CHUNK_BITS 16
+#define MLF_ACC_CHUNK_BITS 18
 #endif
 constexpr int kTileBits = MLF_TILE_BITS;         // log2 of the cells per LDS image
 constexpr uint32_t kTileCells = 1u << kTileBits;
@@ -171,7 +171,11 @@ struct BinPlan {
     uint32_t *fine_cursor;        // [n_tiles * kCursorStride]  records placed so far (zeroed)
     uint32_t *tile_start;         // [n_tiles+1] exclusive scan of hist
     uint32_t *coarse_part_start;  // [n_coarse+1] partition steps before each coarse range
-    uint32_t *chunk_start;        // [n_tiles+1] accumulate work items before each tile
+    uint32_t *chunk_start;        // [n_tiles+1] accumulate work items of the tiles that are not hot,
+                                  //             before each tile
+    uint32_t *hot_chunk_start;    // [kMaxCoarse+1] accumulate work items before each hot tile; the hot
+                                  //             tiles' items come first in the launch
+    uint32_t *hot_tile;           // [kMaxCoarse] tile of each hot digit
     uint32_t *tmp_start;          // [n_coarse+1] first record of each coarse range in tmp
     uint32_t *digit_start;        // [kMaxCoarse] first output index of each digit of the coarse level:
                                   //              in tmp for a coarse range, in sorted for a hot tile
@@ -493,6 +497,7 @@ __global__ __launch_bounds__(kScanThreads) void plan_kernel(const BinPlan plan)
         if ((word >> (b & 31)) & 1u) {
             const uint32_t slot = plan.hot_before[b >> 5] + __popc(word & ((1u << (b & 31)) - 1u));
             plan.digit_start[n_coarse + slot] = tile_start[b];
+            plan.hot_tile[slot] = b;
         }
     }
 
@@ -509,9 +514,22 @@ __global__ __launch_bounds__(kScanThreads) void plan_kernel(const BinPlan plan)
     block_exclusive_scan(
         n_coarse, [&](uint32_t c) { return (cold_records(c) + kPartTile - 1) / kPartTile; },
         plan.coarse_part_start, scratch);
-    // Accumulate work items (kAccChunk records each) per tile.
+    // Accumulate work items (kAccChunk records each): those of the hot tiles
+    // first, so that the long ones start early, then the others in tile order.
+    __syncthreads();
+    __threadfence_block();
+    const uint32_t n_hot = plan.hot_before[kHotWords];
+    const uint32_t *hot_tile = plan.hot_tile;
     block_exclusive_scan(
-        n_tiles, [=](uint32_t j) { return (hist[j] + kAccChunk - 1) / kAccChunk; },
+        kMaxCoarse,
+        [=](uint32_t slot) { return slot < n_hot ? (hist[hot_tile[slot]] + kAccChunk - 1) / kAccChunk : 0u; },
+        plan.hot_chunk_start, scratch);
+    block_exclusive_scan(
+        n_tiles,
+        [=](uint32_t j) {
+            const bool hot = (hot_bits[j >> 5] >> (j & 31)) & 1u;
+            return hot ? 0u : (hist[j] + kAccChunk - 1) / kAccChunk;
+        },
         plan.chunk_start, scratch);
 }
 
@@ -787,19 +805,26 @@ __global__ __launch_bounds__(kAccThreads) void accumulate_kernel(int32_t *__rest
     constexpr int kGroupsPerLane = kTileCells / 4 / kAccThreads;
     __shared__ __attribute__((aligned(16))) int32_t image[kTileCells];
     __shared__ uint32_t s_tile;
-    const uint32_t g = blockIdx.x;
-    if (g >= plan.chunk_start[plan.n_tiles]) return;          // uniform
+    __shared__ uint32_t s_first;                  // work items before this tile's, in its list
+    const uint32_t n_hot_items = plan.hot_chunk_start[kMaxCoarse];
+    if (blockIdx.x >= n_hot_items + plan.chunk_start[plan.n_tiles]) return;      // uniform
+    const bool hot = blockIdx.x < n_hot_items;
+    const uint32_t g = hot ? blockIdx.x : blockIdx.x - n_hot_items;               // item in its list
+    const uint32_t *start = hot ? plan.hot_chunk_start : plan.chunk_start;
     if (threadIdx.x < 64) {
-        const uint32_t t = owner_of(plan.chunk_start, plan.n_tiles, g);
-        if (threadIdx.x == 0) s_tile = t;
+        const uint32_t i = owner_of(start, hot ? kMaxCoarse : plan.n_tiles, g);
+        if (threadIdx.x == 0) {
+            s_tile = hot ? plan.hot_tile[i] : i;
+            s_first = i;
+        }
     }
     i32x4 *image4 = reinterpret_cast<i32x4 *>(image);
 #pragma unroll
     for (int k = 0; k < kGroupsPerLane; ++k) image4[k * kAccThreads + threadIdx.x] = i32x4{0, 0, 0, 0};
     __syncthreads();
     const uint32_t tile = s_tile;
-    const uint32_t chunks = plan.chunk_start[tile + 1] - plan.chunk_start[tile];
-    const uint32_t begin = plan.tile_start[tile] + (g - plan.chunk_start[tile]) * kAccChunk;
+    const uint32_t chunks = start[s_first + 1] - start[s_first];
+    const uint32_t begin = plan.tile_start[tile] + (g - start[s_first]) * kAccChunk;
     const uint32_t end = min(begin + kAccChunk, plan.tile_start[tile + 1]);
     if (wide_records(plan)) {
         accumulate_records<true>(image, plan.sorted, begin, end);
@@ -1019,6 +1044,8 @@ size_t plan_layout(int32_t V, int32_t T, long long n, char *ws, BinPlan *plan)
     char *tile_start = take(sizeof(uint32_t) * (n_tiles + 1));
     char *coarse_part_start = take(sizeof(uint32_t) * (n_coarse + 1));
     char *chunk_start = take(sizeof(uint32_t) * (n_tiles + 1));
+    char *hot_chunk_start = take(sizeof(uint32_t) * (kMaxCoarse + 1));
+    char *hot_tile = take(sizeof(uint32_t) * kMaxCoarse);
     char *tmp_start = take(sizeof(uint32_t) * (n_coarse + 1));
     char *digit_start = take(sizeof(uint32_t) * kMaxCoarse);
     char *hot_bits = take(sizeof(uint32_t) * (kHotWords + 1));
@@ -1033,6 +1060,8 @@ size_t plan_layout(int32_t V, int32_t T, long long n, char *ws, BinPlan *plan)
         plan->tile_start = reinterpret_cast<uint32_t *>(tile_start);
         plan->coarse_part_start = reinterpret_cast<uint32_t *>(coarse_part_start);
         plan->chunk_start = reinterpret_cast<uint32_t *>(chunk_start);
+        plan->hot_chunk_start = reinterpret_cast<uint32_t *>(hot_chunk_start);
+        plan->hot_tile = reinterpret_cast<uint32_t *>(hot_tile);
         plan->tmp_start = reinterpret_cast<uint32_t *>(tmp_start);
         plan->digit_start = reinterpret_cast<uint32_t *>(digit_start);
         plan->hot_bits = reinterpret_cast<uint32_t *>(hot_bits);

@@ -48,7 +48,7 @@ def test_odd_shapes(use_workspace, V, T, K, m):
 @pytest.mark.parametrize("V,T,K,m", [(1, 1, 1, 300_000), (3, 2, 2, 150_000), (32_769, 1, 1, 290_000),
                                      (1, 32_768, 2, 140_000), (7, 9_363, 3, 100_011),
                                      (4_099, 8, 1, 300_000), (2_100_000, 1, 2, 160_000),
-                                     (16_385, 2_048, 2, 450_000)])
+                                     (16_385, 2_048, 2, 450_000), (5, 7, 2, 400_000)])
 def test_binned_path_edge_shapes(V, T, K, m):
     """Shapes chosen around the binned path's geometry: one tile shared by
     several workgroups, a matrix that ends just past a tile boundary, many coarse
