@@ -83,7 +83,6 @@ constexpr int kScanBlock = MLF_SCAN_BLOCK;                    // lanes of a firs
 constexpr int kScanWorkgroups = MLF_SCAN_WGS;                 // first-pass workgroups of a call, about
 constexpr int kScanUnroll = MLF_SCAN_UNROLL;                  // triples per lane and step of the first pass
 constexpr int kScanThreads = 1024;
-constexpr int kScanItems = kMaxTiles / kScanThreads;           // 16
 // The binned path has a fixed cost (six launches, one accumulate workgroup per
 // non-empty tile); the direct path is cheaper below about this many triples
 // (measured crossovers: 0.25 M triples on a 31-tile matrix, 2 M on 3,052 tiles).
@@ -378,39 +377,44 @@ __global__ __launch_bounds__(kThreads) void clear_kernel(uint32_t *p, uint32_t n
     if (i < n) p[i] = 0;
 }
 
-// Exclusive prefix sum over up to kMaxTiles values with one workgroup of
-// kScanThreads lanes: lane i owns kScanItems consecutive values.
-// `value(j)` gives input j; out[j] receives the sum of inputs before j and
-// out[n] the total.  `scratch` is kScanThreads words of LDS.
-template <typename F>
-__device__ void block_exclusive_scan(uint32_t n, F value, uint32_t *out, uint32_t *scratch)
+// Exclusive prefix sums of N values per lane over the kScanThreads lanes of
+// the workgroup: shuffles inside each wavefront, then the wavefront totals
+// through LDS.  excl[k] = sum of v[k] over the lanes before this one, total[k] =
+// sum over all lanes.  Two barriers; `wave_sums` is reused by the next call.
+constexpr int kScanWaves = kScanThreads / 64;
+
+template <int N>
+__device__ __forceinline__ void block_scan(const uint32_t (&v)[N], uint32_t (&excl)[N],
+                                           uint32_t (&total)[N], uint32_t (*wave_sums)[kScanWaves])
 {
-    const uint32_t first = threadIdx.x * kScanItems;
-    uint32_t local[kScanItems];
-    uint32_t sum = 0;
+    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    uint32_t incl[N];
 #pragma unroll
-    for (int i = 0; i < kScanItems; ++i) {
-        const uint32_t j = first + i;
-        local[i] = j < n ? value(j) : 0u;
-        sum += local[i];
+    for (int k = 0; k < N; ++k) incl[k] = v[k];
+    for (int off = 1; off < 64; off <<= 1) {
+#pragma unroll
+        for (int k = 0; k < N; ++k) {
+            const uint32_t up = __shfl_up(incl[k], off, 64);
+            if (lane >= static_cast<uint32_t>(off)) incl[k] += up;
+        }
     }
-    scratch[threadIdx.x] = sum;
+    if (lane == 63) {
+#pragma unroll
+        for (int k = 0; k < N; ++k) wave_sums[k][wave] = incl[k];
+    }
     __syncthreads();
-    // Hillis-Steele scan of the kScanThreads partial sums.
-    for (int off = 1; off < kScanThreads; off <<= 1) {
-        const uint32_t add = threadIdx.x >= static_cast<uint32_t>(off) ? scratch[threadIdx.x - off] : 0u;
-        __syncthreads();
-        scratch[threadIdx.x] += add;
-        __syncthreads();
-    }
-    uint32_t run = scratch[threadIdx.x] - sum;     // exclusive prefix of this lane
 #pragma unroll
-    for (int i = 0; i < kScanItems; ++i) {
-        const uint32_t j = first + i;
-        if (j < n) out[j] = run;
-        run += local[i];
+    for (int k = 0; k < N; ++k) {
+        uint32_t before = 0, all = 0;
+#pragma unroll
+        for (int w = 0; w < kScanWaves; ++w) {
+            const uint32_t t = wave_sums[k][w];
+            before += static_cast<uint32_t>(w) < wave ? t : 0u;
+            all += t;
+        }
+        excl[k] = before + incl[k] - v[k];
+        total[k] = all;
     }
-    if (threadIdx.x == kScanThreads - 1) out[n] = scratch[kScanThreads - 1];
     __syncthreads();
 }
 
@@ -425,7 +429,12 @@ __device__ void block_exclusive_scan(uint32_t n, F value, uint32_t *out, uint32_
 // smallest power-of-two fraction of the total that leaves no more hot tiles
 // than spare digits.  They are published as a bitmap plus, per bitmap word, the
 // number of hot tiles before it, so that a lane finds the digit of a tile with
-// two LDS reads and a population count.
+// one LDS read and a population count.
+//
+// Lane i looks after the tiles i, i + kScanThreads, ... (one per round); the
+// record counts are kept in LDS, and every table over the tiles is a running
+// block scan over the rounds.  (The rounds are loops, not unrolled: the kernel
+// runs once per call, and straight-line code would be fetched from memory once.)
 #ifndef MLF_HOT_SHIFTS
 #define MLF_HOT_SHIFTS 24
 #endif
@@ -433,28 +442,41 @@ constexpr int kHotShifts = MLF_HOT_SHIFTS;     // a hot tile holds at least tota
 
 __global__ __launch_bounds__(kScanThreads) void plan_kernel(const BinPlan plan)
 {
-    __shared__ uint32_t scratch[kScanThreads];
+    static_assert(kMaxCoarse <= kScanThreads, "the tables over coarse digits take one round");
+    __shared__ uint32_t wave_sums[3][kScanWaves];
     __shared__ uint32_t tiles_at_least[kHotShifts];
     __shared__ uint32_t hot_in_range[kMaxCoarse];     // hot records per coarse range
     __shared__ uint32_t s_threshold;
-    const uint32_t *hist = plan.hist;
+    __shared__ uint32_t h[kMaxTiles];                 // records per tile
     const uint32_t n_tiles = plan.n_tiles;
     const uint32_t n_coarse = plan.n_coarse;
-    block_exclusive_scan(n_tiles, [=](uint32_t j) { return hist[j]; }, plan.tile_start, scratch);
-    __threadfence_block();
-    const uint32_t *tile_start = plan.tile_start;
-    const uint32_t total = tile_start[n_tiles];
+    const uint32_t lane = threadIdx.x & 63;
 
-    // Threshold of the hot tiles.  (All tile loops below run whole wavefronts.)
     if (threadIdx.x < kHotShifts) tiles_at_least[threadIdx.x] = 0;
     if (threadIdx.x < kMaxCoarse) hot_in_range[threadIdx.x] = 0;
-    __syncthreads();
+
+    // tile_start: exclusive scan of the histogram.
+    uint32_t total = 0;
+#pragma unroll 1
     for (uint32_t base = 0; base < n_tiles; base += kScanThreads) {
         const uint32_t b = base + threadIdx.x;
-        const uint32_t h = b < n_tiles ? hist[b] : 0u;
+        const uint32_t v[1] = {b < n_tiles ? plan.hist[b] : 0u};
+        h[b] = v[0];
+        uint32_t e[1], t[1];
+        block_scan<1>(v, e, t, wave_sums);
+        if (b < n_tiles) plan.tile_start[b] = total + e[0];
+        total += t[0];
+    }
+    if (threadIdx.x == 0) plan.tile_start[n_tiles] = total;
+
+    // Threshold of the hot tiles.
+#pragma unroll 1
+    for (uint32_t base = 0; base < n_tiles; base += kScanThreads) {
+        const uint32_t mine = h[base + threadIdx.x];
+#pragma unroll 1
         for (int j = 0; j < kHotShifts; ++j) {
-            const unsigned long long heavy = __ballot(h != 0 && h >= (total >> j));
-            if ((threadIdx.x & 63) == 0 && heavy != 0) {
+            const unsigned long long heavy = __ballot(mine != 0 && mine >= (total >> j));
+            if (lane == 0 && heavy != 0) {
                 lds_fetch_add(&tiles_at_least[j], static_cast<uint32_t>(__popcll(heavy)));
             }
         }
@@ -471,66 +493,71 @@ __global__ __launch_bounds__(kScanThreads) void plan_kernel(const BinPlan plan)
     __syncthreads();
     const uint32_t threshold = s_threshold;
 
-    // Bitmap of the hot tiles (all kHotWords words are written) and the hot
-    // records of every coarse range.
+    // Hot tiles: bitmap (every word of it is written), digit of each (its rank
+    // among the hot tiles), hot records per coarse range; and the accumulate
+    // work items (kAccChunk records each) of the tiles that are not hot.
+    uint32_t n_hot = 0, n_items = 0;
+#pragma unroll 1
     for (uint32_t base = 0; base < kMaxTiles; base += kScanThreads) {
         const uint32_t b = base + threadIdx.x;
-        const uint32_t h = b < n_tiles ? hist[b] : 0u;
-        const bool hot = h != 0 && h >= threshold;
+        const uint32_t mine = base < n_tiles ? h[b] : 0u;
+        const bool hot = mine != 0 && mine >= threshold;
         const unsigned long long mask = __ballot(hot);
-        if ((threadIdx.x & 63) == 0) {
+        if (lane == 0) {
             plan.hot_bits[b >> 5] = static_cast<uint32_t>(mask);
             plan.hot_bits[(b >> 5) + 1] = static_cast<uint32_t>(mask >> 32);
         }
-        if (hot) lds_fetch_add(&hot_in_range[b >> kFineBits], h);
-    }
-    __syncthreads();
-    __threadfence_block();
-    const uint32_t *hot_bits = plan.hot_bits;
-    block_exclusive_scan(kHotWords, [=](uint32_t w) { return static_cast<uint32_t>(__popc(hot_bits[w])); },
-                         plan.hot_before, scratch);
-    __threadfence_block();
-    // Hot digits follow the coarse ranges, in tile order; their records go to
-    // the tile's place in `sorted`.
-    for (uint32_t b = threadIdx.x; b < n_tiles; b += kScanThreads) {
-        const uint32_t word = hot_bits[b >> 5];
-        if ((word >> (b & 31)) & 1u) {
-            const uint32_t slot = plan.hot_before[b >> 5] + __popc(word & ((1u << (b & 31)) - 1u));
-            plan.digit_start[n_coarse + slot] = tile_start[b];
-            plan.hot_tile[slot] = b;
+        uint32_t e[2] = {0, 0}, t[2] = {0, 0};
+        if (base < n_tiles) {                                 // uniform
+            const uint32_t v[2] = {hot ? 1u : 0u, hot ? 0u : (mine + kAccChunk - 1) / kAccChunk};
+            block_scan<2>(v, e, t, wave_sums);
         }
+        const uint32_t slot = n_hot + e[0];
+        if ((threadIdx.x & 31) == 0) plan.hot_before[b >> 5] = slot;
+        if (hot) {
+            plan.hot_tile[slot] = b;
+            plan.digit_start[n_coarse + slot] = plan.tile_start[b];      // this lane wrote it
+            lds_fetch_add(&hot_in_range[b >> kFineBits], mine);
+        }
+        if (b < n_tiles) plan.chunk_start[b] = n_items + e[1];
+        n_hot += t[0];
+        n_items += t[1];
     }
-
-    // Records of each coarse range that still go through the fine level.
-    auto cold_records = [&](uint32_t c) {
-        const uint32_t lo = c << kFineBits;
-        const uint32_t hi = min(lo + kFinePerCoarse, n_tiles);
-        return tile_start[hi] - tile_start[lo] - hot_in_range[c];
-    };
-    block_exclusive_scan(n_coarse, cold_records, plan.tmp_start, scratch);
-    __threadfence_block();
-    for (uint32_t c = threadIdx.x; c < n_coarse; c += kScanThreads) plan.digit_start[c] = plan.tmp_start[c];
-    // Partition steps (kPartTile records each) per coarse range.
-    block_exclusive_scan(
-        n_coarse, [&](uint32_t c) { return (cold_records(c) + kPartTile - 1) / kPartTile; },
-        plan.coarse_part_start, scratch);
-    // Accumulate work items (kAccChunk records each): those of the hot tiles
-    // first, so that the long ones start early, then the others in tile order.
+    if (threadIdx.x == 0) {
+        plan.hot_before[kHotWords] = n_hot;
+        plan.chunk_start[n_tiles] = n_items;
+    }
     __syncthreads();
     __threadfence_block();
-    const uint32_t n_hot = plan.hot_before[kHotWords];
-    const uint32_t *hot_tile = plan.hot_tile;
-    block_exclusive_scan(
-        kMaxCoarse,
-        [=](uint32_t slot) { return slot < n_hot ? (hist[hot_tile[slot]] + kAccChunk - 1) / kAccChunk : 0u; },
-        plan.hot_chunk_start, scratch);
-    block_exclusive_scan(
-        n_tiles,
-        [=](uint32_t j) {
-            const bool hot = (hot_bits[j >> 5] >> (j & 31)) & 1u;
-            return hot ? 0u : (hist[j] + kAccChunk - 1) / kAccChunk;
-        },
-        plan.chunk_start, scratch);
+
+    // Per coarse range: the records that still go through the fine level and
+    // their partition steps (kPartTile records each); per hot digit: the
+    // accumulate work items of its tile, which come first in that launch so
+    // that the long ones start early.
+    {
+        const uint32_t c = threadIdx.x;
+        uint32_t cold = 0;
+        if (c < n_coarse) {
+            const uint32_t lo = c << kFineBits;
+            const uint32_t hi = min(lo + kFinePerCoarse, n_tiles);
+            cold = plan.tile_start[hi] - plan.tile_start[lo] - hot_in_range[c];
+        }
+        uint32_t hot_items = 0;
+        if (c < n_hot) hot_items = (h[plan.hot_tile[c]] + kAccChunk - 1) / kAccChunk;
+        const uint32_t v[3] = {cold, (cold + kPartTile - 1) / kPartTile, hot_items};
+        uint32_t e[3], t[3];
+        block_scan<3>(v, e, t, wave_sums);
+        if (c < n_coarse) {
+            plan.tmp_start[c] = e[0];
+            plan.digit_start[c] = e[0];
+            plan.coarse_part_start[c] = e[1];
+        }
+        if (c == n_coarse) {
+            plan.tmp_start[c] = t[0];
+            plan.coarse_part_start[c] = t[1];
+        }
+        if (c <= kMaxCoarse) plan.hot_chunk_start[c] = c < kMaxCoarse ? e[2] : t[2];
+    }
 }
 
 // Largest index i in [0, n) with start[i] <= g, for a non-decreasing start[] with
