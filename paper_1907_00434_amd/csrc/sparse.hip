@@ -12,8 +12,9 @@
 //
 // Binned path (needs scratch).  Triples are first grouped by the 128 KiB tile
 // of counts[] they fall into (a two-level counting sort: 64 fine tiles per
-// coarse range, so that every partition step writes long contiguous runs).
-// One workgroup then owns a tile at a time: it accumulates the tile's records
+// coarse range, so that every partition step writes contiguous runs; the
+// heaviest tiles get a digit of their own at the coarse level and skip the fine
+// one).  One workgroup then owns a tile at a time: it accumulates the tile's records
 // with LDS atomics into a private 32768-cell image and merges the image into
 // counts[] with contiguous 128-bit read-modify-writes (or contiguous atomics
 // when a heavy tile is shared by several workgroups).  Global atomic traffic
@@ -82,7 +83,7 @@ constexpr uint32_t kAccChunk = 1u << MLF_ACC_CHUNK_BITS;   // records per accumu
 constexpr int kScanBlock = MLF_SCAN_BLOCK;                    // lanes of a first-pass workgroup
 constexpr int kScanWorkgroups = MLF_SCAN_WGS;                 // first-pass workgroups of a call, about
 constexpr int kScanUnroll = MLF_SCAN_UNROLL;                  // triples per lane and step of the first pass
-constexpr int kScanThreads = 1024;
+constexpr int kPlanThreads = 1024;                            // lanes of the one plan workgroup
 // The binned path has a fixed cost (six launches, one accumulate workgroup per
 // non-empty tile); the direct path is cheaper below about this many triples
 // (measured crossovers: 0.25 M triples on a 31-tile matrix, 2 M on 3,052 tiles).
@@ -377,15 +378,15 @@ __global__ __launch_bounds__(kThreads) void clear_kernel(uint32_t *p, uint32_t n
     if (i < n) p[i] = 0;
 }
 
-// Exclusive prefix sums of N values per lane over the kScanThreads lanes of
+// Exclusive prefix sums of N values per lane over the kPlanThreads lanes of
 // the workgroup: shuffles inside each wavefront, then the wavefront totals
 // through LDS.  excl[k] = sum of v[k] over the lanes before this one, total[k] =
 // sum over all lanes.  Two barriers; `wave_sums` is reused by the next call.
-constexpr int kScanWaves = kScanThreads / 64;
+constexpr int kPlanWaves = kPlanThreads / 64;
 
 template <int N>
 __device__ __forceinline__ void block_scan(const uint32_t (&v)[N], uint32_t (&excl)[N],
-                                           uint32_t (&total)[N], uint32_t (*wave_sums)[kScanWaves])
+                                           uint32_t (&total)[N], uint32_t (*wave_sums)[kPlanWaves])
 {
     const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     uint32_t incl[N];
@@ -407,7 +408,7 @@ __device__ __forceinline__ void block_scan(const uint32_t (&v)[N], uint32_t (&ex
     for (int k = 0; k < N; ++k) {
         uint32_t before = 0, all = 0;
 #pragma unroll
-        for (int w = 0; w < kScanWaves; ++w) {
+        for (int w = 0; w < kPlanWaves; ++w) {
             const uint32_t t = wave_sums[k][w];
             before += static_cast<uint32_t>(w) < wave ? t : 0u;
             all += t;
@@ -431,7 +432,7 @@ __device__ __forceinline__ void block_scan(const uint32_t (&v)[N], uint32_t (&ex
 // number of hot tiles before it, so that a lane finds the digit of a tile with
 // one LDS read and a population count.
 //
-// Lane i looks after the tiles i, i + kScanThreads, ... (one per round); the
+// Lane i looks after the tiles i, i + kPlanThreads, ... (one per round); the
 // record counts are kept in LDS, and every table over the tiles is a running
 // block scan over the rounds.  (The rounds are loops, not unrolled: the kernel
 // runs once per call, and straight-line code would be fetched from memory once.)
@@ -440,10 +441,10 @@ __device__ __forceinline__ void block_scan(const uint32_t (&v)[N], uint32_t (&ex
 #endif
 constexpr int kHotShifts = MLF_HOT_SHIFTS;     // a hot tile holds at least total >> (kHotShifts - 1) records
 
-__global__ __launch_bounds__(kScanThreads) void plan_kernel(const BinPlan plan)
+__global__ __launch_bounds__(kPlanThreads) void plan_kernel(const BinPlan plan)
 {
-    static_assert(kMaxCoarse <= kScanThreads, "the tables over coarse digits take one round");
-    __shared__ uint32_t wave_sums[3][kScanWaves];
+    static_assert(kMaxCoarse <= kPlanThreads, "the tables over coarse digits take one round");
+    __shared__ uint32_t wave_sums[3][kPlanWaves];
     __shared__ uint32_t tiles_at_least[kHotShifts];
     __shared__ uint32_t hot_in_range[kMaxCoarse];     // hot records per coarse range
     __shared__ uint32_t s_threshold;
@@ -458,7 +459,7 @@ __global__ __launch_bounds__(kScanThreads) void plan_kernel(const BinPlan plan)
     // tile_start: exclusive scan of the histogram.
     uint32_t total = 0;
 #pragma unroll 1
-    for (uint32_t base = 0; base < n_tiles; base += kScanThreads) {
+    for (uint32_t base = 0; base < n_tiles; base += kPlanThreads) {
         const uint32_t b = base + threadIdx.x;
         const uint32_t v[1] = {b < n_tiles ? plan.hist[b] : 0u};
         h[b] = v[0];
@@ -471,7 +472,7 @@ __global__ __launch_bounds__(kScanThreads) void plan_kernel(const BinPlan plan)
 
     // Threshold of the hot tiles.
 #pragma unroll 1
-    for (uint32_t base = 0; base < n_tiles; base += kScanThreads) {
+    for (uint32_t base = 0; base < n_tiles; base += kPlanThreads) {
         const uint32_t mine = h[base + threadIdx.x];
 #pragma unroll 1
         for (int j = 0; j < kHotShifts; ++j) {
@@ -498,7 +499,7 @@ __global__ __launch_bounds__(kScanThreads) void plan_kernel(const BinPlan plan)
     // work items (kAccChunk records each) of the tiles that are not hot.
     uint32_t n_hot = 0, n_items = 0;
 #pragma unroll 1
-    for (uint32_t base = 0; base < kMaxTiles; base += kScanThreads) {
+    for (uint32_t base = 0; base < kMaxTiles; base += kPlanThreads) {
         const uint32_t b = base + threadIdx.x;
         const uint32_t mine = base < n_tiles ? h[b] : 0u;
         const bool hot = mine != 0 && mine >= threshold;
@@ -1188,7 +1189,7 @@ extern "C" mlf_status mlf_sparse_scatter_add(int32_t *counts, int32_t *totals, i
         scan_triples_kernel<true, false><<<scan_grid, dim3(kScanBlock), hist_lds, s>>>(a, plan);
     }
     if (!launched()) return MLF_EHIP;
-    plan_kernel<<<dim3(1), dim3(kScanThreads), 0, s>>>(plan);
+    plan_kernel<<<dim3(1), dim3(kPlanThreads), 0, s>>>(plan);
     if (!launched()) return MLF_EHIP;
     const unsigned steps_per_buffer = static_cast<unsigned>((longest + kPartTile - 1) / kPartTile);
     coarse_partition_kernel<<<dim3(steps_per_buffer, static_cast<unsigned>(used)), dim3(kPartThreads), 0, s>>>(a, plan);
