@@ -56,3 +56,45 @@ def test_random_dense_cases(block):
             except AssertionError as e:
                 raise AssertionError(f"seed {seed}, call {call}: {e}") from e
     torch.cuda.synchronize()
+
+
+def random_sparse_case(seed):
+    """Shape, skew, number and raggedness of the buffers, delta range (both
+    record formats), invalid triples and word-id permutation drawn at random;
+    sizes on both sides of the point where the binned path takes over."""
+    rng = np.random.default_rng(seed)
+    V = int(rng.choice([1, 7, 300, 5_003, 40_000, 250_000]))
+    T = int(rng.choice([1, 3, 64, 1_000, 4_097]))
+    while V * T > 100_000_000:
+        V //= 2
+    K = int(rng.choice([1, 2, 5, 9, 64]))
+    total = int(rng.choice([50_000, 300_000, 700_000, 1_500_000]))
+    cfg = W.scaled(W.CONFIGS["cfg5"], V=V, T=T, K=K, m=max(total // K, 1),
+                   zipf_s=float(rng.choice([0.0, 0.8, 1.1, 2.0])), index=int(seed % 100_000))
+    d = W.sparse_inputs(cfg, "cuda", init=str(rng.choice(["zeros", "random"])),
+                        permute_ids=bool(rng.random() < 0.5), n_invalid=int(rng.integers(0, 9)))
+    # ragged buffers: cut each at a random length (some empty)
+    d["triples"] = [t[: int(rng.integers(0, t.shape[0] + 1))] if rng.random() < 0.4 else t
+                    for t in d["triples"]]
+    mode = rng.integers(0, 3)
+    if mode == 1:      # a few large deltas: the call switches to 8-byte records
+        for t in d["triples"]:
+            if t.shape[0] > 10:
+                t[3::1013, 2] = int(rng.integers(-2 ** 31, 2 ** 31))
+    elif mode == 2:    # every delta small but not +-1
+        for t in d["triples"]:
+            t[:, 2] *= int(rng.integers(1, 1023))
+    return cfg, d
+
+
+@pytest.mark.parametrize("block", range(4))
+def test_random_sparse_cases(block):
+    from parity import run_sparse
+    for seed in range(block * 6, block * 6 + 6):
+        cfg, d = random_sparse_case(1907_00434 + 1000 + seed)
+        for use_workspace in (False, True):
+            try:
+                run_sparse(cfg, d, use_workspace, threads=4)
+            except AssertionError as e:
+                raise AssertionError(f"seed {seed}, workspace {use_workspace}: {e}") from e
+    torch.cuda.synchronize()
