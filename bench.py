@@ -235,11 +235,18 @@ def cpu_baseline(job, W, torch):
 
     t_multi = timed(threads, 6.0)
     t_single = timed(1, 4.0)
+    model = ""
+    try:
+        with open("/proc/cpuinfo") as f:
+            model = next((l.split(":", 1)[1].strip() for l in f if l.startswith("model name")), "")
+    except OSError:
+        pass
     return {
         "value": round(nbytes / t_multi / 1e9, 3), "unit": "GB/s", "cores": threads,
         "kind": "oracle", "sample": sample,
         "elements_per_s": round(n_units / t_multi, 1),
         "single_thread_value": round(nbytes / t_single / 1e9, 3),
+        "cpu_model": model, "host_cpus": os.cpu_count(),
     }
 
 
