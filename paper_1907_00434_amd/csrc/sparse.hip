@@ -116,14 +116,24 @@ struct Record {
 constexpr int kCoarseShift = kTileBits + kFineBits;
 constexpr int32_t kSmallDeltaLimit = 1 << (31 - kCoarseShift);
 
+// The one-word forms of a record.
+__device__ __forceinline__ uint32_t pack_tmp(Record r)
+{
+    return (r.cell & ((1u << kCoarseShift) - 1)) | (static_cast<uint32_t>(r.delta) << kCoarseShift);
+}
+
+__device__ __forceinline__ uint32_t pack_sorted(Record r)
+{
+    return (r.cell & (kTileCells - 1)) | (static_cast<uint32_t>(r.delta) << kTileBits);
+}
+
 template <bool WIDE>
 __device__ __forceinline__ void store_tmp(void *tmp, uint32_t i, Record r)
 {
     if constexpr (WIDE) {
         static_cast<Record *>(tmp)[i] = r;
     } else {
-        static_cast<uint32_t *>(tmp)[i] =
-            (r.cell & ((1u << kCoarseShift) - 1)) | (static_cast<uint32_t>(r.delta) << kCoarseShift);
+        static_cast<uint32_t *>(tmp)[i] = pack_tmp(r);
     }
 }
 
@@ -145,8 +155,7 @@ __device__ __forceinline__ void store_sorted(void *sorted, uint32_t i, Record r)
     if constexpr (WIDE) {
         static_cast<Record *>(sorted)[i] = r;
     } else {
-        static_cast<uint32_t *>(sorted)[i] =
-            (r.cell & (kTileCells - 1)) | (static_cast<uint32_t>(r.delta) << kTileBits);
+        static_cast<uint32_t *>(sorted)[i] = pack_sorted(r);
     }
 }
 
@@ -587,19 +596,34 @@ __device__ __forceinline__ uint32_t owner_of(const uint32_t *start, uint32_t n, 
 //   rec[i], live[i]  the lane's records and whether each exists
 //   digit_of(cell)   digit of a record
 //   reserve(d, n)    output index where this step's n records of digit d go
+// Eight-byte records (WIDE) are staged as they are and placed when they are
+// written out:
 //   emit(d, i, r)    writes record r of digit d at output index i
+// One-word records are packed and given their output index when they are
+// staged, so that writing them out is a copy:
+//   pack(d, r)       the word to store for record r of digit d; bit 31 of the
+//                    result's `where` selects the output array
+//   copy(where, w)   stores word w at output index (where & 0x7fffffff)
+struct Staged {
+    uint32_t word;
+    uint32_t where;
+};
+
 struct PartitionLds {
-    Record stage[kPartTile];
+    union {
+        Record wide[kPartTile];
+        Staged narrow[kPartTile];
+    } stage;
     uint32_t count[kMaxCoarse];
     uint32_t offset[kMaxCoarse];
     uint32_t dest[kMaxCoarse];
     uint32_t total;
 };
 
-template <typename DigitOf, typename Reserve, typename Emit>
+template <bool WIDE, typename DigitOf, typename Reserve, typename Emit, typename Pack, typename Copy>
 __device__ __forceinline__ void partition_step(PartitionLds &s, const Record (&rec)[kPartItems],
                                                const bool (&live)[kPartItems], DigitOf digit_of,
-                                               Reserve reserve, Emit emit)
+                                               Reserve reserve, Emit emit, Pack pack, Copy copy)
 {
     static_assert(kMaxCoarse == 256 && kPartThreads >= 256, "one wavefront scans 4 digits per lane");
     uint32_t dig[kPartItems], rank[kPartItems];
@@ -638,16 +662,33 @@ __device__ __forceinline__ void partition_step(PartitionLds &s, const Record (&r
         if (mine != 0) s.dest[threadIdx.x] = reserve(threadIdx.x, mine);
     }
     __syncthreads();
+    if constexpr (WIDE) {
 #pragma unroll
-    for (int i = 0; i < kPartItems; ++i) {
-        if (live[i]) s.stage[s.offset[dig[i]] + rank[i]] = rec[i];
-    }
-    __syncthreads();
-    const uint32_t total = s.total;
-    for (uint32_t i = threadIdx.x; i < total; i += kPartThreads) {
-        const Record r = s.stage[i];
-        const uint32_t d = digit_of(r.cell);
-        emit(d, s.dest[d] + (i - s.offset[d]), r);
+        for (int i = 0; i < kPartItems; ++i) {
+            if (live[i]) s.stage.wide[s.offset[dig[i]] + rank[i]] = rec[i];
+        }
+        __syncthreads();
+        const uint32_t total = s.total;
+        for (uint32_t i = threadIdx.x; i < total; i += kPartThreads) {
+            const Record r = s.stage.wide[i];
+            const uint32_t d = digit_of(r.cell);
+            emit(d, s.dest[d] + (i - s.offset[d]), r);
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < kPartItems; ++i) {
+            if (live[i]) {
+                Staged e = pack(dig[i], rec[i]);
+                e.where |= s.dest[dig[i]] + rank[i];
+                s.stage.narrow[s.offset[dig[i]] + rank[i]] = e;
+            }
+        }
+        __syncthreads();
+        const uint32_t total = s.total;
+        for (uint32_t i = threadIdx.x; i < total; i += kPartThreads) {
+            const Staged e = s.stage.narrow[i];
+            copy(e.where, e.word);
+        }
     }
 }
 
@@ -685,7 +726,9 @@ __device__ __forceinline__ void coarse_partition_body(PartitionLds &s, HotLds &h
     __syncthreads();
     const uint32_t n_coarse = plan.n_coarse;
     const HotLds *h = &hot;
-    partition_step(
+    uint32_t *tmp_words = static_cast<uint32_t *>(plan.tmp);
+    uint32_t *sorted_words = static_cast<uint32_t *>(plan.sorted);
+    partition_step<WIDE>(
         s, rec, live,
         [=](uint32_t cell) {
             const uint32_t tile = cell >> kTileBits;
@@ -705,6 +748,13 @@ __device__ __forceinline__ void coarse_partition_body(PartitionLds &s, HotLds &h
             } else {
                 store_sorted<WIDE>(plan.sorted, i, r);
             }
+        },
+        [=](uint32_t d, Record r) {
+            return d < n_coarse ? Staged{pack_tmp(r), 0u} : Staged{pack_sorted(r), 0x80000000u};
+        },
+        [=](uint32_t where, uint32_t word) {
+            uint32_t *out = (where >> 31) != 0 ? sorted_words : tmp_words;
+            out[where & 0x7fffffffu] = word;
         });
 }
 
@@ -745,13 +795,16 @@ __device__ __forceinline__ void fine_partition_body(PartitionLds &s, const BinPl
     }
     if (threadIdx.x < kMaxCoarse) s.count[threadIdx.x] = 0;
     __syncthreads();
-    partition_step(
+    uint32_t *sorted_words = static_cast<uint32_t *>(plan.sorted);
+    partition_step<WIDE>(
         s, rec, live, [](uint32_t cell) { return (cell >> kTileBits) & (kFinePerCoarse - 1); },
         [=](uint32_t f, uint32_t n) {
             const uint32_t tile = first_tile + f;
             return plan.tile_start[tile] + fetch_add_relaxed(plan.fine_cursor + tile * kCursorStride, n);
         },
-        [=](uint32_t, uint32_t i, Record r) { store_sorted<WIDE>(plan.sorted, i, r); });
+        [=](uint32_t, uint32_t i, Record r) { store_sorted<WIDE>(plan.sorted, i, r); },
+        [](uint32_t, Record r) { return Staged{pack_sorted(r), 0u}; },
+        [=](uint32_t where, uint32_t word) { sorted_words[where] = word; });
 }
 
 __global__ __launch_bounds__(kPartThreads) void fine_partition_kernel(const BinPlan plan)
