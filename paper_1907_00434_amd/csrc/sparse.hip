@@ -249,7 +249,8 @@ __device__ __forceinline__ uint32_t wave_rank(uint32_t *counter, uint32_t bin, b
     const unsigned long long group = __ballot(grouped);
     uint32_t base = 0;
     if (static_cast<int>(threadIdx.x & 63) == leader) {
-        base = lds_fetch_add(&counter[lead_bin], static_cast<uint32_t>(__popcll(group)));
+        // (indexed by the lane's own bin, which equals lead_bin here)
+        base = lds_fetch_add(&counter[bin], static_cast<uint32_t>(__popcll(group)));
     }
     base = broadcast(base, leader);
     if (grouped) return base + lanes_below(group);
@@ -734,10 +735,9 @@ __device__ __forceinline__ void coarse_partition_body(PartitionLds &s, HotLds &h
             const uint32_t tile = cell >> kTileBits;
             const uint2 entry = h->word[tile >> 5];
             const uint32_t bit = tile & 31;
-            if ((entry.x >> bit) & 1u) {
-                return n_coarse + entry.y + static_cast<uint32_t>(__popc(entry.x & ((1u << bit) - 1u)));
-            }
-            return tile >> kFineBits;
+            const uint32_t hot_digit =
+                n_coarse + entry.y + static_cast<uint32_t>(__popc(entry.x & ((1u << bit) - 1u)));
+            return ((entry.x >> bit) & 1u) != 0 ? hot_digit : tile >> kFineBits;
         },
         [=](uint32_t d, uint32_t n) {
             return plan.digit_start[d] + fetch_add_relaxed(plan.coarse_cursor + d * kCursorStride, n);
