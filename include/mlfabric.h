@@ -251,7 +251,7 @@ mlf_status mlf_sparse_scatter_add(int32_t *counts, int32_t *totals, int32_t V,
 
 /* Scratch the grouped path of mlf_sparse_scatter_add needs for this problem
  * size: about 16 bytes per triple.  0 when that path would not be used: a
- * matrix of more than 2^29 cells, or a batch so small that the direct path is
+ * matrix of more than 2^30 cells, or a batch so small that the direct path is
  * faster (fewer than 262,144 + 600 per 32,768 cells of the matrix triples). */
 size_t mlf_sparse_workspace_bytes(int32_t V, int32_t T, int64_t total_triples);
 

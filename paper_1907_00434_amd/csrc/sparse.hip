@@ -11,7 +11,7 @@
 // per triple.
 //
 // Binned path (needs scratch).  Triples are first grouped by the 128 KiB tile
-// of counts[] they fall into (a two-level counting sort: 64 fine tiles per
+// of counts[] they fall into (a two-level counting sort: 128 fine tiles per
 // coarse range, so that every partition step writes contiguous runs; the
 // heaviest tiles get a digit of their own at the coarse level and skip the fine
 // one).  One workgroup then owns a tile at a time: it accumulates the tile's records
@@ -39,7 +39,7 @@ constexpr int kMaxLdsTopics = 16384;     // totals privatised in LDS up to 64 Ki
 #define MLF_TILE_BITS 15
 #endif
 #ifndef MLF_FINE_BITS
-#define MLF_FINE_BITS 6
+#define MLF_FINE_BITS 7
 #endif
 #ifndef MLF_ACC_THREADS
 #define MLF_ACC_THREADS 1024
@@ -52,7 +52,7 @@ constexpr uint32_t kTileCells = 1u << kTileBits;
 constexpr int kFineBits = MLF_FINE_BITS;         // log2 of the fine tiles per coarse range
 constexpr uint32_t kFinePerCoarse = 1u << kFineBits;
 constexpr uint32_t kMaxCoarse = 256;             // coarse ranges (one counter per lane)
-constexpr uint32_t kMaxTiles = 16384;            // tiles a call may span (LDS histogram, scan)
+constexpr uint32_t kMaxTiles = 32768;            // tiles a call may span (LDS histogram, plan tables)
 constexpr uint32_t kHotWords = kMaxTiles / 32;   // words of the hot-tile bitmap
 #ifndef MLF_PART_THREADS
 #define MLF_PART_THREADS 1024
@@ -289,12 +289,18 @@ __device__ __forceinline__ bool load_triple(const int32_t *tr, long long r, int 
 // of that buffer.  BINNED = false: the direct path (counts[] updated here).
 // BINNED = true: only the per-tile histogram is built.  Both keep the totals in
 // LDS and count the rejected triples.
-// Dynamic LDS: [T totals if LDS_TOTALS][n_tiles histogram if BINNED].
-template <bool BINNED, bool LDS_TOTALS>
+// LDS: [T totals if LDS_TOTALS][n_tiles histogram if BINNED], dynamic up to
+// 64 KiB; BIG = a static array instead, for histograms of up to kMaxTiles tiles
+// with up to kBigTopics totals.
+constexpr int kBigTopics = 4096;
+
+template <bool BINNED, bool LDS_TOTALS, bool BIG = false>
 __global__ __launch_bounds__(kScanBlock) void scan_triples_kernel(const SparseArgs a,
                                                                 const BinPlan plan)
 {
-    extern __shared__ int32_t lds[];
+    extern __shared__ int32_t dynamic_lds[];
+    __shared__ int32_t static_lds[BIG ? kMaxTiles + kBigTopics : 1];
+    int32_t *lds = BIG ? static_lds : dynamic_lds;
     const int T = a.T;
     const bool want_totals = a.totals != nullptr;
     int32_t *lds_totals = lds;
@@ -504,25 +510,23 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const BinPlan plan)
     __syncthreads();
     const uint32_t threshold = s_threshold;
 
-    // Hot tiles: bitmap (every word of it is written), digit of each (its rank
-    // among the hot tiles), hot records per coarse range; and the accumulate
-    // work items (kAccChunk records each) of the tiles that are not hot.
+    // Hot tiles: bitmap (the words that cover the call's tiles), digit of each
+    // (its rank among the hot tiles), hot records per coarse range; and the
+    // accumulate work items (kAccChunk records each) of the tiles that are not hot.
     uint32_t n_hot = 0, n_items = 0;
 #pragma unroll 1
-    for (uint32_t base = 0; base < kMaxTiles; base += kPlanThreads) {
+    for (uint32_t base = 0; base < n_tiles; base += kPlanThreads) {
         const uint32_t b = base + threadIdx.x;
-        const uint32_t mine = base < n_tiles ? h[b] : 0u;
+        const uint32_t mine = h[b];
         const bool hot = mine != 0 && mine >= threshold;
         const unsigned long long mask = __ballot(hot);
         if (lane == 0) {
             plan.hot_bits[b >> 5] = static_cast<uint32_t>(mask);
             plan.hot_bits[(b >> 5) + 1] = static_cast<uint32_t>(mask >> 32);
         }
-        uint32_t e[2] = {0, 0}, t[2] = {0, 0};
-        if (base < n_tiles) {                                 // uniform
-            const uint32_t v[2] = {hot ? 1u : 0u, hot ? 0u : (mine + kAccChunk - 1) / kAccChunk};
-            block_scan<2>(v, e, t, wave_sums);
-        }
+        const uint32_t v[2] = {hot ? 1u : 0u, hot ? 0u : (mine + kAccChunk - 1) / kAccChunk};
+        uint32_t e[2], t[2];
+        block_scan<2>(v, e, t, wave_sums);
         const uint32_t slot = n_hot + e[0];
         if ((threadIdx.x & 31) == 0) plan.hot_before[b >> 5] = slot;
         if (hot) {
@@ -720,7 +724,7 @@ __device__ __forceinline__ void coarse_partition_body(PartitionLds &s, HotLds &h
     }
     // The hot-tile bitmap and the digit counters, while the triples are in flight.
     static_assert(kHotWords <= kPartThreads && kMaxCoarse <= kPartThreads, "one word per lane");
-    if (threadIdx.x < kHotWords) {
+    if (threadIdx.x < (plan.n_tiles + 31) / 32) {       // the words that cover the call's tiles
         hot.word[threadIdx.x] = make_uint2(plan.hot_bits[threadIdx.x], plan.hot_before[threadIdx.x]);
     }
     if (threadIdx.x < kMaxCoarse) s.count[threadIdx.x] = 0;
@@ -1232,14 +1236,17 @@ extern "C" mlf_status mlf_sparse_scatter_add(int32_t *counts, int32_t *totals, i
     clear_kernel<<<dim3((n_clear + kThreads - 1) / kThreads), dim3(kThreads), 0, s>>>(plan.hist, n_clear);
     if (!launched()) return MLF_EHIP;
     const size_t hist_lds = static_cast<size_t>(plan.n_tiles) * sizeof(uint32_t);
-    if (totals_lds + hist_lds > 65536) {    // keep the first pass within 64 KiB of LDS
-        lds_totals = false;
-        totals_lds = 0;
-    }
-    if (lds_totals) {
-        scan_triples_kernel<true, true><<<scan_grid, dim3(kScanBlock), totals_lds + hist_lds, s>>>(a, plan);
+    if (totals_lds + hist_lds <= 65536) {
+        if (lds_totals) {
+            scan_triples_kernel<true, true><<<scan_grid, dim3(kScanBlock), totals_lds + hist_lds, s>>>(a, plan);
+        } else {
+            scan_triples_kernel<true, false><<<scan_grid, dim3(kScanBlock), hist_lds, s>>>(a, plan);
+        }
+    } else if (lds_totals && T <= kBigTopics) {
+        // More than 64 KiB of histogram and totals: the variant with a static array.
+        scan_triples_kernel<true, true, true><<<scan_grid, dim3(kScanBlock), 0, s>>>(a, plan);
     } else {
-        scan_triples_kernel<true, false><<<scan_grid, dim3(kScanBlock), hist_lds, s>>>(a, plan);
+        scan_triples_kernel<true, false, true><<<scan_grid, dim3(kScanBlock), 0, s>>>(a, plan);
     }
     if (!launched()) return MLF_EHIP;
     plan_kernel<<<dim3(1), dim3(kPlanThreads), 0, s>>>(plan);

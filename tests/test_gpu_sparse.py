@@ -60,8 +60,9 @@ def test_binned_path_edge_shapes(V, T, K, m):
 
 
 def test_shapes_the_binned_path_declines():
-    # more than 2^29 cells: no scratch is asked for and the direct path serves
-    assert mlf.mlf_sparse_workspace_bytes(70_000, 8_000, 1_000_000) == 0
+    # more than 2^30 cells: no scratch is asked for and the direct path serves
+    assert mlf.mlf_sparse_workspace_bytes(140_000, 8_000, 100_000_000) == 0
+    assert mlf.mlf_sparse_workspace_bytes(70_000, 8_000, 1_000_000) == 0     # batch too small for 17,090 tiles
     assert mlf.mlf_sparse_workspace_bytes(100, 100, 100) == 0        # tiny batch
     # small batches on a large matrix: the fixed cost per tile would dominate
     assert mlf.mlf_sparse_workspace_bytes(100_000, 1_000, 1_000_000) == 0
@@ -69,6 +70,17 @@ def test_shapes_the_binned_path_declines():
     cfg = recipe(V=70_000, T=8_000, K=1, m=100_000)
     d = W.sparse_inputs(cfg, "cuda", init="zeros")
     run_sparse(cfg, d, True)
+
+
+def test_matrix_of_more_than_16384_tiles():
+    """2.4 GB of counts (18,311 tiles): the first pass keeps its histogram in a
+    static LDS array, and the hot-tile bitmap is used beyond its first half."""
+    cfg = recipe(V=600_000, T=1_000, K=6, m=2_000_000)
+    assert mlf.mlf_sparse_workspace_bytes(cfg.V, cfg.T, cfg.K * cfg.m) > 0
+    d = W.sparse_inputs(cfg, "cuda", init="zeros", permute_ids=True, n_invalid=5)
+    run_sparse(cfg, d, True)
+    del d
+    torch.cuda.empty_cache()
 
 
 @pytest.mark.parametrize("use_workspace", [False, True])
@@ -188,9 +200,9 @@ def test_dense_delta_full_matrix_size():
     torch.cuda.empty_cache()
 
 
-@pytest.mark.parametrize("big", [1023, -1024, 1024, -1025, 2 ** 30, -2 ** 31])
+@pytest.mark.parametrize("big", [511, -512, 512, -513, 1023, 2 ** 30, -2 ** 31])
 def test_binned_path_record_formats(big):
-    """Deltas in [-1024, 1024) travel as 4-byte records through the scratch, any
+    """Deltas in [-512, 512) travel as 4-byte records through the scratch, any
     other delta switches the whole call to 8-byte records: both sides of the
     boundary, and extreme values."""
     cfg = recipe(V=3001, T=500, K=3, m=100_000)
