@@ -142,6 +142,35 @@ def test_sparse_argument_checks():
     assert mlf.mlf_sparse_workspace_bytes(100000, 1000, 0) >= 0
 
 
+def test_sparse_scratch_size_and_path_selection():
+    """Host logic of the sparse call's scratch query: 0 where the direct path
+    serves (small batches, matrices past 2^30 cells), else about 16 bytes per
+    triple, growing with the batch, a multiple of the 256-byte alignment."""
+    ws = mlf.mlf_sparse_workspace_bytes
+    tile = 32_768                                              # cells per tile
+    for V, T in ((100_000, 1_000), (1, 1), (3, 40_000), (1_000_000, 1_000)):
+        tiles = (V * T + tile - 1) // tile
+        least = 262_144 + 600 * tiles
+        assert ws(V, T, least - 1) == 0
+        assert ws(V, T, 0) == 0 and ws(V, T, -5) == 0
+        a, b = ws(V, T, least), ws(V, T, 4 * least)
+        assert 0 < a < b and a % 256 == 0 and b % 256 == 0
+        assert 16 * least <= a <= 16 * least + 64 * tiles * 4 + (1 << 20)
+    assert ws(32_768, 32_768, 10 ** 9) > 0                     # exactly 2^30 cells
+    assert ws(32_769, 32_768, 10 ** 9) == 0                    # one row more
+    assert ws(0, 5, 10 ** 6) == 0 and ws(5, 0, 10 ** 6) == 0
+    assert ws(100_000, 1_000, 2 ** 31) == 0                    # more triples than a 32-bit index
+
+
+def test_norms_scratch_size():
+    ws = mlf.mlf_norms_workspace_bytes
+    assert ws(-1) == 0
+    sizes = [ws(n) for n in (0, 1, 511, 512, 513, 10 ** 6, 10 ** 9)]
+    assert all(x > 0 and x % 16 == 0 for x in sizes)
+    assert sizes == sorted(sizes)
+    assert ws(10 ** 9) <= 40 * 10 ** 6                         # 16 bytes per 512 elements, about
+
+
 def test_dense_delta_argument_checks():
     lib = B.raw()
     counts, d0 = FAKE, FAKE + 0x100000
