@@ -278,8 +278,9 @@ mlf_status mlf_counts_add_dense(int32_t *counts, int32_t *totals, int32_t V, int
                                 const int32_t *const *delta_ptrs, int K,
                                 mlf_stream stream);
 
-/* Static, human-readable name of a status code. */
-const char *mlf_status_string(mlf_status status);
+/* Static, human-readable name of a status code; any other value gives
+ * "unknown mlf_status". */
+const char *mlf_status_string(int status);
 
 #ifdef __cplusplus
 }

@@ -873,7 +873,7 @@ extern "C" mlf_status mlf_divergence(const float *w_server, const float *w_repli
     return finish_norms(partials, grid, norms_partials_capacity(n), dist_sq, 1, s) ? MLF_OK : MLF_EHIP;
 }
 
-extern "C" const char *mlf_status_string(mlf_status status)
+extern "C" const char *mlf_status_string(int status)
 {
     switch (status) {
     case MLF_OK: return "MLF_OK";
