@@ -48,7 +48,8 @@ typedef enum {
     MLF_EINVAL = -1,        /* bad argument (see each call)                    */
     MLF_EALIGN = -2,        /* a device pointer is not aligned to its element  */
     MLF_EUNSUPPORTED = -3,  /* K > MLF_MAX_K                                   */
-    MLF_EHIP = -4           /* the HIP runtime refused the launch              */
+    MLF_EHIP = -4,          /* the HIP runtime refused the launch              */
+    MLF_STATUS_INT32 = 0x7fffffff   /* not a status: makes every int a valid value of the type */
 } mlf_status;
 
 typedef enum { MLF_F32 = 0, MLF_BF16 = 1 } mlf_dtype;
@@ -280,7 +281,7 @@ mlf_status mlf_counts_add_dense(int32_t *counts, int32_t *totals, int32_t V, int
 
 /* Static, human-readable name of a status code; any other value gives
  * "unknown mlf_status". */
-const char *mlf_status_string(int status);
+const char *mlf_status_string(mlf_status status);
 
 #ifdef __cplusplus
 }

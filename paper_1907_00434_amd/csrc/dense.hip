@@ -873,7 +873,7 @@ extern "C" mlf_status mlf_divergence(const float *w_server, const float *w_repli
     return finish_norms(partials, grid, norms_partials_capacity(n), dist_sq, 1, s) ? MLF_OK : MLF_EHIP;
 }
 
-extern "C" const char *mlf_status_string(int status)
+extern "C" const char *mlf_status_string(mlf_status status)
 {
     switch (status) {
     case MLF_OK: return "MLF_OK";
@@ -881,6 +881,7 @@ extern "C" const char *mlf_status_string(int status)
     case MLF_EALIGN: return "MLF_EALIGN: device pointer not aligned to its element size";
     case MLF_EUNSUPPORTED: return "MLF_EUNSUPPORTED: more than MLF_MAX_K updates or buffers";
     case MLF_EHIP: return "MLF_EHIP: HIP launch failed";
+    default: break;
     }
     return "unknown mlf_status";
 }
