@@ -10,9 +10,9 @@
  *    the scheduler's decisions.  They are read before the call returns and may
  *    be freed or changed right after it.
  *  - "device" arguments are HIP device pointers owned by the caller.  The
- *    library allocates no memory, keeps no state between calls and frees
- *    nothing.  Device buffers must stay valid until the stream has run the
- *    enqueued work.
+ *    library allocates no memory and frees nothing; the only state it keeps
+ *    between calls is the scratch array of mlf_divergence_static (below).
+ *    Device buffers must stay valid until the stream has run the enqueued work.
  *  - Every call only enqueues kernels on `stream` (a hipStream_t; NULL is the
  *    default stream) and returns; it never synchronises the device.
  *  - Errors are reported through the return code only; nothing is enqueued when
@@ -47,7 +47,7 @@ typedef enum {
     MLF_OK = 0,
     MLF_EINVAL = -1,        /* bad argument (see each call)                    */
     MLF_EALIGN = -2,        /* a device pointer is not aligned to its element  */
-    MLF_EUNSUPPORTED = -3,  /* K > MLF_MAX_K                                   */
+    MLF_EUNSUPPORTED = -3,  /* K > MLF_MAX_K, or n > MLF_STATIC_MAX_N          */
     MLF_EHIP = -4,          /* the HIP runtime refused the launch              */
     MLF_STATUS_INT32 = 0x7fffffff   /* not a status: makes every int a valid value of the type */
 } mlf_status;
@@ -57,6 +57,7 @@ typedef enum { MLF_F32 = 0, MLF_BF16 = 1 } mlf_dtype;
 typedef void *mlf_stream;   /* a hipStream_t */
 
 #define MLF_MAX_K 64        /* most updates (or triple buffers) per call */
+#define MLF_STATIC_MAX_N (1ll << 28)   /* most elements mlf_divergence_static takes */
 
 /*
  * Aggregator (Sec. 4 "Architecture": aggregators compute the (weighted) sum of
@@ -210,6 +211,29 @@ mlf_status mlf_apply_grouped_norms(float *model, float *momentum,
 mlf_status mlf_divergence(const float *w_server, const float *w_replica, int64_t n,
                           double *dist_sq, void *workspace, size_t workspace_bytes,
                           mlf_stream stream);
+
+/*
+ * mlf_divergence for callers that cannot allocate device memory and so have no
+ * workspace to pass: code running under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments without the workspace, same
+ * kernels, same result bit for bit.  The partial sums go to an array of
+ * (MLF_STATIC_MAX_N / 512 + 4162) * 16 bytes (about 8.1 MiB) that is part of the
+ * library's device code: every GPU the library runs on holds one copy until the
+ * process ends.  The call allocates and frees nothing; the first call on a
+ * device looks up the address of that device's copy (make it outside a graph
+ * capture) and later calls reuse it.
+ *
+ * All calls on one GPU share that array: two calls whose work may overlap on the
+ * device (different streams, or graph branches that run side by side) race and
+ * give wrong distances; order them on one stream or with events.  The array
+ * keeps the previous call's partial sums; every entry a call reads it has
+ * written first, so nothing needs clearing.
+ *
+ * MLF_EUNSUPPORTED: n > MLF_STATIC_MAX_N (use mlf_divergence with a workspace),
+ * or a device ordinal above 63.  Otherwise as mlf_divergence.
+ */
+mlf_status mlf_divergence_static(const float *w_server, const float *w_replica, int64_t n,
+                                 double *dist_sq, mlf_stream stream);
 
 /*
  * LDA count deltas (Sec. 6 "Datasets and ML models": each LDA worker computes a

@@ -16,6 +16,7 @@ from .binding import (  # noqa: F401
     mlf_apply_grouped_norms,
     mlf_counts_add_dense,
     mlf_divergence,
+    mlf_divergence_static,
     mlf_norms_workspace_bytes,
     mlf_apply_ordered,
     mlf_sparse_scatter_add,

@@ -14,6 +14,7 @@ import torch
 from . import build as _build
 
 MLF_MAX_K = 64
+MLF_STATIC_MAX_N = 1 << 28
 MLF_OK, MLF_EINVAL, MLF_EALIGN, MLF_EUNSUPPORTED, MLF_EHIP = 0, -1, -2, -3, -4
 MLF_F32, MLF_BF16 = 0, 1
 
@@ -71,6 +72,9 @@ def raw():
     lib.mlf_divergence.argtypes = [_c.c_void_p, _c.c_void_p, _c.c_int64, _c.c_void_p,
                                    _c.c_void_p, _c.c_size_t, _c.c_void_p]
     lib.mlf_divergence.restype = _c.c_int
+    lib.mlf_divergence_static.argtypes = [_c.c_void_p, _c.c_void_p, _c.c_int64, _c.c_void_p,
+                                          _c.c_void_p]
+    lib.mlf_divergence_static.restype = _c.c_int
     lib.mlf_sparse_scatter_add.argtypes = [_c.c_void_p, _c.c_void_p, _c.c_int32, _c.c_int32,
                                            vpp, _c.POINTER(_c.c_int64), _c.c_int,
                                            _c.c_void_p, _c.c_size_t, _c.c_void_p,
@@ -247,6 +251,18 @@ def mlf_divergence(w_server, w_replica, dist_sq, workspace, n=None, stream=None,
         raise ValueError("dist_sq must be a float64 device tensor")
     st = raw().mlf_divergence(_ptr(w_server), _ptr(w_replica), n, _ptr(dist_sq), _ptr(workspace),
                               _nbytes(workspace), _stream(stream))
+    return _done(st, check)
+
+
+def mlf_divergence_static(w_server, w_replica, dist_sq, n=None, stream=None, check=True):
+    """mlf_divergence without a workspace (the library's own scratch array)."""
+    n = w_server.numel() if n is None else int(n)
+    _state(w_server, n, "w_server")
+    _state(w_replica, n, "w_replica")
+    if dist_sq.dtype != torch.float64 or dist_sq.numel() < 1:
+        raise ValueError("dist_sq must be a float64 device tensor")
+    st = raw().mlf_divergence_static(_ptr(w_server), _ptr(w_replica), n, _ptr(dist_sq),
+                                     _stream(stream))
     return _done(st, check)
 
 

@@ -18,6 +18,8 @@
 
 #include <stdint.h>
 
+#include <atomic>
+
 #include "mlfabric.h"
 
 #pragma clang fp contract(off)
@@ -782,7 +784,7 @@ extern "C" mlf_status mlf_apply_grouped(float *model, float *momentum,
 
 // Partial sums a norms variant may need: one pair per workgroup of the
 // (64 lanes x 2 groups) shape, for either layout of the elements.
-static size_t norms_partials_capacity(long long n)
+static constexpr size_t norms_partials_capacity(long long n)
 {
     return static_cast<size_t>(n / (64 * 2 * 4)) + 2 + static_cast<size_t>(kMaxScalarGroups);
 }
@@ -844,16 +846,12 @@ extern "C" mlf_status mlf_apply_grouped_norms(float *model, float *momentum,
                                          norms_partials_capacity(n));
 }
 
-extern "C" mlf_status mlf_divergence(const float *w_server, const float *w_replica, int64_t n,
-                                     double *dist_sq, void *workspace, size_t workspace_bytes,
-                                     mlf_stream stream)
+// Squared distance of two vectors with the partial sums in `partials` (room for
+// norms_partials_capacity(n) + kFinishSlices pairs).  Every partial that is read
+// has been written by this call, so the buffer needs no clearing.
+static mlf_status divergence_launch(const float *w_server, const float *w_replica, long long n,
+                                    double *dist_sq, double *partials, hipStream_t s)
 {
-    if (w_server == nullptr || w_replica == nullptr || dist_sq == nullptr || n < 0) return MLF_EINVAL;
-    if (workspace == nullptr || workspace_bytes < mlf_norms_workspace_bytes(n)) return MLF_EINVAL;
-    if (reinterpret_cast<uintptr_t>(w_server) % 4 != 0 || reinterpret_cast<uintptr_t>(w_replica) % 4 != 0 ||
-        reinterpret_cast<uintptr_t>(workspace) % 16 != 0 || reinterpret_cast<uintptr_t>(dist_sq) % 8 != 0) {
-        return MLF_EALIGN;
-    }
     const bool aligned16 = reinterpret_cast<uintptr_t>(w_server) % 16 == 0 &&
                            reinterpret_cast<uintptr_t>(w_replica) % 16 == 0;
     const long long n_vec = aligned16 ? n / 4 * 4 : 0;
@@ -862,8 +860,6 @@ extern "C" mlf_status mlf_divergence(const float *w_server, const float *w_repli
     long long tiles_s = (n - n_vec + 63) / 64;
     if (tiles_s > kMaxScalarGroups) tiles_s = kMaxScalarGroups;
     if (static_cast<size_t>(tiles_v + tiles_s) > norms_partials_capacity(n)) return MLF_EUNSUPPORTED;
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    double *partials = static_cast<double *>(workspace);
     const unsigned grid = static_cast<unsigned>(tiles_v + tiles_s);
     if (grid > 0) {
         divergence_kernel<<<dim3(grid), dim3(64), 0, s>>>(w_server, w_replica, n, n_vec,
@@ -873,13 +869,86 @@ extern "C" mlf_status mlf_divergence(const float *w_server, const float *w_repli
     return finish_norms(partials, grid, norms_partials_capacity(n), dist_sq, 1, s) ? MLF_OK : MLF_EHIP;
 }
 
+static mlf_status divergence_check(const float *w_server, const float *w_replica, long long n,
+                                   const double *dist_sq)
+{
+    if (w_server == nullptr || w_replica == nullptr || dist_sq == nullptr || n < 0) return MLF_EINVAL;
+    if (reinterpret_cast<uintptr_t>(w_server) % 4 != 0 || reinterpret_cast<uintptr_t>(w_replica) % 4 != 0 ||
+        reinterpret_cast<uintptr_t>(dist_sq) % 8 != 0) {
+        return MLF_EALIGN;
+    }
+    return MLF_OK;
+}
+
+extern "C" mlf_status mlf_divergence(const float *w_server, const float *w_replica, int64_t n,
+                                     double *dist_sq, void *workspace, size_t workspace_bytes,
+                                     mlf_stream stream)
+{
+    if (w_server == nullptr || w_replica == nullptr || dist_sq == nullptr || n < 0) return MLF_EINVAL;
+    if (workspace == nullptr || workspace_bytes < mlf_norms_workspace_bytes(n)) return MLF_EINVAL;
+    if (reinterpret_cast<uintptr_t>(workspace) % 16 != 0) return MLF_EALIGN;
+    const mlf_status st = divergence_check(w_server, w_replica, n, dist_sq);
+    if (st != MLF_OK) return st;
+    return divergence_launch(w_server, w_replica, n, dist_sq, static_cast<double *>(workspace),
+                             static_cast<hipStream_t>(stream));
+}
+
+// ---------------------------------------------------------------------------
+// The divergence for callers that cannot allocate: its partial sums live in a
+// file-scope device array instead of a caller's workspace.  Every GPU holds its
+// own copy of the array at its own address; the address is looked up once per
+// device (hipGetSymbolAddress, with that device current) and kept.  The array's
+// name is only ever used in that lookup: host code passes the looked-up pointer.
+// ---------------------------------------------------------------------------
+constexpr size_t kStaticScratchBytes =
+    (norms_partials_capacity(MLF_STATIC_MAX_N) + kFinishSlices) * 2 * sizeof(double);
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+static std::atomic<double *> g_scratch_ptr[kMaxDevices];
+
+// The current device's copy of `scratch`.
+static mlf_status static_scratch(double **out)
+{
+    int device = -1;
+    if (hipGetDevice(&device) != hipSuccess) return MLF_EHIP;
+    if (device < 0 || device >= kMaxDevices) return MLF_EUNSUPPORTED;
+    double *p = g_scratch_ptr[device].load(std::memory_order_acquire);
+    if (p == nullptr) {
+        void *address = nullptr;
+        if (hipGetSymbolAddress(&address, HIP_SYMBOL(scratch)) != hipSuccess || address == nullptr) {
+            return MLF_EHIP;
+        }
+        p = static_cast<double *>(address);
+        // Threads that race here have looked up the same address.
+        g_scratch_ptr[device].store(p, std::memory_order_release);
+    }
+    *out = p;
+    return MLF_OK;
+}
+
+extern "C" mlf_status mlf_divergence_static(const float *w_server, const float *w_replica,
+                                            int64_t n, double *dist_sq, mlf_stream stream)
+{
+    const mlf_status st = divergence_check(w_server, w_replica, n, dist_sq);
+    if (st != MLF_OK) return st;
+    if (n > MLF_STATIC_MAX_N) return MLF_EUNSUPPORTED;
+    double *partials = nullptr;
+    const mlf_status found = static_scratch(&partials);
+    if (found != MLF_OK) return found;
+    return divergence_launch(w_server, w_replica, n, dist_sq, partials,
+                             static_cast<hipStream_t>(stream));
+}
+
 extern "C" const char *mlf_status_string(mlf_status status)
 {
     switch (status) {
     case MLF_OK: return "MLF_OK";
     case MLF_EINVAL: return "MLF_EINVAL: invalid argument";
     case MLF_EALIGN: return "MLF_EALIGN: device pointer not aligned to its element size";
-    case MLF_EUNSUPPORTED: return "MLF_EUNSUPPORTED: more than MLF_MAX_K updates or buffers";
+    case MLF_EUNSUPPORTED:
+        return "MLF_EUNSUPPORTED: beyond a limit of the library (MLF_MAX_K updates or buffers, "
+               "MLF_STATIC_MAX_N elements for the call without workspace)";
     case MLF_EHIP: return "MLF_EHIP: HIP launch failed";
     default: break;
     }

@@ -24,7 +24,8 @@ def test_every_declared_symbol_is_exported():
     names = declared_functions()
     assert {"mlf_aggregate", "mlf_apply_ordered", "mlf_aggregate_apply", "mlf_apply_grouped",
             "mlf_sparse_scatter_add", "mlf_sparse_workspace_bytes", "mlf_aggregate_norm",
-            "mlf_apply_grouped_norms", "mlf_norms_workspace_bytes", "mlf_divergence", "mlf_counts_add_dense",
+            "mlf_apply_grouped_norms", "mlf_norms_workspace_bytes", "mlf_divergence", "mlf_divergence_static",
+            "mlf_counts_add_dense",
             "mlf_status_string"} <= set(names)
     lib = ctypes.CDLL(mlf.library_path())
     for name in names:
@@ -187,3 +188,20 @@ def test_binding_refuses_host_tensors():
     import torch
     with pytest.raises(ValueError):
         mlf.mlf_aggregate([torch.zeros(4)], [0], None, torch.zeros(4))
+
+
+def test_divergence_static_argument_checks():
+    """The entry point without a workspace rejects sizes beyond its scratch array
+    (and the other bad arguments) before it touches the device."""
+    lib = B.raw()
+    a, b, out = FAKE, FAKE + 0x100000, FAKE + 0x200000
+    assert lib.mlf_divergence_static(a, b, B.MLF_STATIC_MAX_N + 1, out, None) == B.MLF_EUNSUPPORTED
+    assert "MLF_STATIC_MAX_N" in mlf.mlf_status_string(B.MLF_EUNSUPPORTED)
+    assert lib.mlf_divergence_static(None, b, 8, out, None) == B.MLF_EINVAL
+    assert lib.mlf_divergence_static(a, None, 8, out, None) == B.MLF_EINVAL
+    assert lib.mlf_divergence_static(a, b, 8, None, None) == B.MLF_EINVAL
+    assert lib.mlf_divergence_static(a, b, -1, out, None) == B.MLF_EINVAL
+    assert lib.mlf_divergence_static(a + 2, b, 8, out, None) == B.MLF_EALIGN
+    assert lib.mlf_divergence_static(a, b, 8, out + 4, None) == B.MLF_EALIGN
+    text = open(os.path.join(ROOT, "include", "mlfabric.h")).read()
+    assert re.search(r"#define MLF_STATIC_MAX_N \(1ll << 28\)", text) and B.MLF_STATIC_MAX_N == 1 << 28
