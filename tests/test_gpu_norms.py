@@ -189,3 +189,43 @@ def test_replica_lags_then_catches_up():
     mlf.mlf_divergence(w_s, w_x, dist, ws)
     swapped = float(np.sum((g * (u1 - u2)) ** 2))
     assert dist.item() > 0 and abs(dist.item() / swapped - 1) < 1e-2
+
+
+# ---- sizes whose partial sums are reduced in two stages (16,384 pairs and more) --------
+
+def test_divergence_two_stage_reduction():
+    """17,000,005 elements: 16,602 partial pairs from the 128-bit region plus the
+    ragged tail's; the same path the benchmark times on 61 M elements."""
+    n = 17_000_005
+    g = torch.Generator(device="cuda")
+    g.manual_seed(4242)
+    a = torch.randn(n, generator=g, device="cuda")
+    b = a + torch.randn(n, generator=g, device="cuda") * 1e-3
+    dist = torch.full((1,), -1.0, dtype=torch.float64, device="cuda")
+    ws = workspace(n)
+    mlf.mlf_divergence(a, b, dist, ws)
+    first = dist.item()
+    ref = oracle.sum_sq_diff(W.to_host(a), W.to_host(b), threads=16)
+    assert close(first, ref), (first, ref)
+    ws.fill_(0xff)                                    # the scratch's old contents do not matter
+    mlf.mlf_divergence(a, b, dist, ws)
+    assert dist.item() == first
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_aggregate_norm_two_stage_reduction(dtype):
+    n = 17_000_005                                    # 33,204 partial pairs
+    cfg = W.scaled(W.CONFIGS["cfg2"], n=n, K=3, dtype=dtype)
+    d = W.dense_inputs(cfg, "cuda")
+    ups_h = [W.to_host(u) for u in d["updates"]]
+    out = torch.empty(n, device="cuda")
+    norm = torch.full((1,), -1.0, dtype=torch.float64, device="cuda")
+    ws = workspace(n)
+    mlf.mlf_aggregate_norm(d["updates"], d["order"], d["weights"], out, norm, ws)
+    ref = oracle.aggregate(ups_h, d["order"], d["weights"], threads=16)
+    assert_same_bits(out, ref, "aggregate_norm out")
+    first = norm.item()
+    assert close(first, oracle.sum_sq(ref, threads=16)), (first, oracle.sum_sq(ref, threads=16))
+    ws.fill_(0xff)
+    mlf.mlf_aggregate_norm(d["updates"], d["order"], d["weights"], out, norm, ws)
+    assert norm.item() == first

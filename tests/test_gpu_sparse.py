@@ -83,6 +83,19 @@ def test_matrix_of_more_than_16384_tiles():
     torch.cuda.empty_cache()
 
 
+@pytest.mark.parametrize("V,T", [(1_000_000, 1_000), (1_048_576, 1_024)])
+def test_matrices_at_the_binned_paths_upper_limit(V, T):
+    """30,518 tiles (4 GB of counts) and exactly 32,768 tiles = 2^30 cells, the
+    most the binned path serves: histogram, plan tables and hot-tile bitmap at
+    their full size.  Zero initial counts, permuted word ids, every cell compared."""
+    cfg = recipe(V=V, T=T, K=8, m=2_600_000)
+    assert mlf.mlf_sparse_workspace_bytes(cfg.V, cfg.T, cfg.K * cfg.m) > 0
+    d = W.sparse_inputs(cfg, "cuda", init="zeros", permute_ids=True, n_invalid=5)
+    run_sparse(cfg, d, True)
+    del d
+    torch.cuda.empty_cache()
+
+
 @pytest.mark.parametrize("use_workspace", [False, True])
 def test_hand_case_ragged_buffers_and_optional_arguments(use_workspace, golden):
     g = {k: np.array([int(x) for x in v], dtype=np.int32)
