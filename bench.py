@@ -9,11 +9,14 @@ SGD with momentum); `--workload cfg1..cfg5` selects another one.  "Effective"
 bandwidth is ALGORITHMIC bytes (each update once, model and momentum read and
 written once) divided by time, so redundant traffic lowers it.
 
-Prints one JSON line.
+Prints one JSON line.  Besides the headline it carries `dense_roofline`, the
+fraction of the 8 TB/s peak of every dense configuration with the smallest one
+named (`min_dense_frac`), and `rows`, every other call on its configuration.
 """
 from __future__ import annotations
 
 import argparse
+import hashlib
 import json
 import os
 import sys
@@ -24,17 +27,8 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
-
-# HBM bytes per launch from hardware counters (FETCH_SIZE x 2.000 + WRITE_SIZE x
-# 1.000, the factors a plain 1 GiB copy calibrates), taken with the kernels as
-# they are in this tree (summary kept under profiles/).  cfg5 = whole call.
-MEASURED_TRAFFIC_BYTES = {
-    "cfg1": 25.3e6,
-    "cfg2": 2044.6e6,
-    "cfg3": 8798.4e6,
-    "cfg4": 4427.4e6,
-    "cfg5": 2770.3e6,
-}
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+KERNEL_SOURCES = ["paper_1907_00434_amd/csrc/dense.hip", "paper_1907_00434_amd/csrc/sparse.hip"]
 
 
 def parse_args():
@@ -52,6 +46,30 @@ def parse_args():
                     help="also run a plain 1 GiB device copy a few times (reference for "
                          "hardware byte counters)")
     return ap.parse_args()
+
+
+def kernel_source_digest():
+    """sha256 over the kernel sources: ties a counter measurement to the code it
+    was taken on."""
+    h = hashlib.sha256()
+    for rel in KERNEL_SOURCES:
+        with open(os.path.join(ROOT, rel), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()
+
+
+def measured_traffic(workload):
+    """HBM bytes per launch from the hardware-counter summary kept under
+    profiles/ (FETCH_SIZE and WRITE_SIZE, scaled by a plain copy), or None when
+    there is none for this workload or the kernels have changed since."""
+    try:
+        with open(TRAFFIC_FILE) as f:
+            rec = json.load(f)
+    except (OSError, ValueError):
+        return None
+    if rec.get("kernel_source_sha256") != kernel_source_digest():
+        return None
+    return rec.get("traffic_bytes", {}).get(workload)
 
 
 class DenseJob:
@@ -79,6 +97,7 @@ class DenseJob:
         self.bytes = (cfg.in_bytes * len(d["order"]) + state) * cfg.n
         self.units = len(d["order"]) * cfg.n          # update elements consumed per step
         self.kernel = "dense_kernel"
+        self.state_bytes = (state - 4 if self.call == "aggregate" else state) // 2 * cfg.n
 
     def step(self):
         d, m = self.d, self.mlf
@@ -99,6 +118,11 @@ class DenseJob:
 
 
 class SparseJob:
+    """cfg5.  Algorithmic bytes: 12 per triple, one 4-byte read and write of
+    every DISTINCT cell the batch touches, the totals read and written once.
+    The distinct cells are counted on the device here (one flag per cell, set
+    by the valid triples); the CPU-baseline leg recounts them with the oracle."""
+
     def __init__(self, cfg, mlf, W, torch, permute_ids=False):
         self.cfg, self.mlf = cfg, mlf
         self.call = "sparse_scatter_add" + (" (permuted word ids)" if permute_ids else "")
@@ -106,7 +130,15 @@ class SparseJob:
         total = cfg.K * cfg.m
         nbytes = mlf.mlf_sparse_workspace_bytes(cfg.V, cfg.T, total)
         self.ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device="cuda:0")
-        self.bytes = cfg.algorithmic_bytes()
+        seen = torch.zeros(cfg.V * cfg.T, dtype=torch.bool, device="cuda:0")
+        for t in self.d["triples"]:
+            ok = (t[:, 0] >= 0) & (t[:, 0] < cfg.V) & (t[:, 1] >= 0) & (t[:, 1] < cfg.T)
+            seen[(t[ok, 0].long() * cfg.T + t[ok, 1].long())] = True
+        self.distinct_cells = int(seen.sum().item())
+        self.distinct_source = "device (flags over the flat indices of the valid triples)"
+        del seen
+        self.bytes = cfg.algorithmic_bytes(self.distinct_cells)
+        self.bytes_per_triple_rule = 20 * total      # 12 B + one 4-byte read-modify-write per triple
         self.units = total                             # triples per step
         self.kernel = "scatter"
 
@@ -134,7 +166,9 @@ class DivergenceJob:
 
 
 class DenseDeltaJob:
-    """The LDA update as 8 dense int32 delta matrices (2 % of the cells non-zero)."""
+    """The LDA update as 8 dense int32 delta matrices (2 % of the cells non-zero).
+    Bytes: every delta matrix once, and one read and one write of the cells
+    whose summed delta is not zero (a cell whose deltas cancel needs neither)."""
 
     def __init__(self, cfg, mlf, torch, K=8):
         self.cfg, self.mlf, self.call = cfg, mlf, "counts_add_dense"
@@ -146,9 +180,16 @@ class DenseDeltaJob:
             vals = torch.randint(-5, 6, (cells,), generator=g, device="cuda:0", dtype=torch.int32)
             keep = torch.rand(cells, generator=g, device="cuda:0") < 0.02
             self.mats.append(torch.where(keep, vals, torch.zeros_like(vals)))
+        total = torch.zeros(cells, dtype=torch.int32, device="cuda:0")
+        for m_ in self.mats:
+            total += m_
+        self.changed_cells = int((total != 0).sum().item())
+        del total
         self.counts = torch.zeros(cells, dtype=torch.int32, device="cuda:0")
         self.totals = torch.zeros(cfg.T, dtype=torch.int32, device="cuda:0")
-        self.bytes, self.units = (4 * K + 8) * cells, K * cells
+        self.bytes = 4 * K * cells + 8 * self.changed_cells + 8 * cfg.T
+        self.bytes_nominal = (4 * K + 8) * cells
+        self.units = K * cells
 
     def step(self):
         self.mlf.mlf_counts_add_dense(self.counts, self.totals, self.cfg.V, self.cfg.T, self.mats)
@@ -189,30 +230,33 @@ def time_each(torch, job, steps, between=None):
 
 
 def cpu_baseline(job, W, torch):
-    """The oracle, as it stands, on a bounded sample of the same workload."""
+    """The oracle, as it stands, on the WHOLE configuration of the headline
+    workload: repeated for a few seconds with all host threads, then with one."""
     import numpy as np
 
     import oracle
     threads = min(16, len(os.sched_getaffinity(0)))
     cfg, d = job.cfg, job.d
+    extra = {}
     if job.call.startswith("sparse_scatter_add"):
-        tr = [W.to_host(t[: 500_000]) for t in d["triples"][:8]]
+        tr = [W.to_host(t) for t in d["triples"]]
         counts = np.zeros(cfg.V * cfg.T, dtype=np.int32)
         totals = np.zeros(cfg.T, dtype=np.int32)
         n_units = sum(t.shape[0] for t in tr)
-        nbytes = 20 * n_units
-        sample = f"first 500,000 triples of 8 of the {cfg.K} buffers into the full {cfg.V}x{cfg.T} matrix"
+        distinct = oracle.touched_cells(cfg.V, cfg.T, tr, threads=threads)
+        extra = {"distinct_cells": distinct, "distinct_cells_agree_with_device": distinct == job.distinct_cells}
+        nbytes = 12 * n_units + 8 * distinct + 8 * cfg.T
+        sample = f"the whole configuration: {n_units:,} triples into the {cfg.V}x{cfg.T} matrix"
 
         def run(th):
             oracle.scatter_add(counts, totals, cfg.V, cfg.T, tr, threads=th)
     else:
-        n_s = min(cfg.n, 4_000_000)
-        ups = [W.to_host(u[:n_s]) for u in d["updates"]]
-        w = W.to_host(d["model"][:n_s])
-        h = W.to_host(d["momentum"][:n_s]) if d["momentum"] is not None else None
-        n_units = len(d["order"]) * n_s
-        nbytes = job.bytes // cfg.n * n_s
-        sample = f"first {n_s:,} of {cfg.n:,} elements of all {cfg.K} updates"
+        ups = [W.to_host(u) for u in d["updates"]]
+        w = W.to_host(d["model"])
+        h = W.to_host(d["momentum"]) if d["momentum"] is not None else None
+        n_units = len(d["order"]) * cfg.n
+        nbytes = job.bytes
+        sample = f"the whole configuration: all {cfg.n:,} elements of all {cfg.K} updates"
 
         def run(th):
             if job.call == "apply_ordered":
@@ -230,11 +274,11 @@ def cpu_baseline(job, W, torch):
             run(th)
             reps += 1
             el = time.perf_counter() - t0
-            if el >= budget_s and reps >= 2:
-                return el / reps
+            if el >= budget_s or reps >= 50:
+                return el / reps, reps
 
-    t_multi = timed(threads, 6.0)
-    t_single = timed(1, 4.0)
+    t_multi, reps_multi = timed(threads, 6.0)
+    t_single, reps_single = timed(1, 6.0)
     model = ""
     try:
         with open("/proc/cpuinfo") as f:
@@ -243,10 +287,12 @@ def cpu_baseline(job, W, torch):
         pass
     return {
         "value": round(nbytes / t_multi / 1e9, 3), "unit": "GB/s", "cores": threads,
-        "kind": "oracle", "sample": sample,
+        "kind": "oracle", "sample": sample, "repetitions": reps_multi,
+        "seconds_per_repetition": round(t_multi, 4),
         "elements_per_s": round(n_units / t_multi, 1),
         "single_thread_value": round(nbytes / t_single / 1e9, 3),
-        "cpu_model": model, "host_cpus": os.cpu_count(),
+        "single_thread_repetitions": reps_single,
+        "cpu_model": model, "host_cpus": os.cpu_count(), **extra,
     }
 
 
@@ -300,7 +346,11 @@ def main():
         "config": {
             "workload": f"{args.workload}: {job.call}",
             "K": cfg.K,
-            **({"V": cfg.V, "T": cfg.T, "triples": cfg.K * cfg.m} if args.workload == "cfg5"
+            **({"V": cfg.V, "T": cfg.T, "triples": cfg.K * cfg.m,
+                "distinct_cells_touched": job.distinct_cells,
+                "distinct_cells_counted_on": job.distinct_source,
+                "bytes_at_20_per_triple (not used)": job.bytes_per_triple_rule}
+               if args.workload == "cfg5"
                else {"n": cfg.n, "update_dtype": cfg.dtype, "momentum": cfg.momentum,
                      "lr": cfg.lr, "mu": cfg.mu}),
             "algorithmic_bytes_per_step": job.bytes,
@@ -311,13 +361,17 @@ def main():
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": round(achieved / HBM_PEAK_GBS, 4),
-            "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload),
+            "traffic": measured_traffic(args.workload),
             "kernel": job.kernel,
             "avg_launch_ms": round(event_ms, 5),
         },
     }
     if args.workload == "cfg5":
         line["dtype"] = "int32"
+    elif job.state_bytes <= 256 << 20:
+        line["roofline"]["note"] = ("model and momentum (%.0f MB) stay in the 256 MiB memory-side cache between the "
+                                    "back-to-back timed calls; the row with the caches evicted before each launch "
+                                    "is the HBM-only figure" % (job.state_bytes / 1e6))
 
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(job, W, torch)
@@ -334,6 +388,7 @@ def main():
         del job
         torch.cuda.empty_cache()
         rows = {}
+        dense_frac = {}
         plan = [("cfg1", None), ("cfg2", "aggregate"), ("cfg2", None), ("cfg3", None),
                 ("cfg3", "apply_grouped"), ("cfg2", "apply_grouped"),
                 ("cfg2", "apply_grouped_norms"), ("cfg3", "apply_grouped_norms"),
@@ -344,19 +399,34 @@ def main():
             key = f"{name}:{j.call}"
             med, best = time_each(torch, j, 20)
             rows[key] = {"ms": round(ev, 5), "median_ms": round(med, 5), "min_ms": round(best, 5),
+                         "algorithmic_bytes": j.bytes,
                          "GB/s": round(j.bytes / ev / 1e6, 1),
                          "frac_of_peak": round(j.bytes / ev / 1e6 / HBM_PEAK_GBS, 4),
                          "units_per_s": round(j.units / (ev * 1e-3), 1)}
-            if name == "cfg1":
-                # cfg1 fits the caches: also time it with a 1 GiB read-modify-write
-                # between launches, which evicts L2 and the Infinity Cache.
-                thrash = torch.zeros(1 << 28, dtype=torch.float32, device="cuda:0")
-                med, best = time_each(torch, j, 20, between=lambda: thrash.add_(1.0))
-                rows[key + " (caches evicted before each launch)"] = {
+            if isinstance(j, SparseJob):
+                rows[key]["distinct_cells_touched"] = j.distinct_cells
+                rows[key]["GB/s_at_20_bytes_per_triple"] = round(j.bytes_per_triple_rule / ev / 1e6, 1)
+            if isinstance(j, DenseDeltaJob):
+                rows[key]["cells_with_nonzero_sum"] = j.changed_cells
+                rows[key]["GB/s_at_nominal_bytes (every cell read and written)"] = round(j.bytes_nominal / ev / 1e6, 1)
+            if isinstance(j, DenseJob) and name != "cfg1":
+                dense_frac[key] = rows[key]["frac_of_peak"]
+            if name in ("cfg1", "cfg2") and call is None:
+                # The state of cfg1 / cfg2 fits the caches: also time the call after a
+                # read-only pass over 2 GiB, which evicts L2 and the memory-side cache
+                # and leaves no dirty lines behind for the timed call to write back
+                # (the HBM-only figure).
+                thrash = torch.zeros(1 << 29, dtype=torch.float32, device="cuda:0")
+                med, best = time_each(torch, j, 20, between=lambda: thrash.sum())
+                cold = key + " (caches evicted before each launch)"
+                rows[cold] = {
                     "median_ms": round(med, 5), "min_ms": round(best, 5),
                     "GB/s": round(j.bytes / med / 1e6, 1),
                     "frac_of_peak": round(j.bytes / med / 1e6 / HBM_PEAK_GBS, 4)}
+                if name == "cfg2":
+                    dense_frac[cold] = rows[cold]["frac_of_peak"]
                 del thrash
+            if name == "cfg1":
                 # Back-to-back calls from Python are launch-bound at this size;
                 # recorded into a HIP graph (20 calls per replay) they are not.
                 side = torch.cuda.Stream()
@@ -385,6 +455,14 @@ def main():
             del j
             torch.cuda.empty_cache()
         line["rows"] = rows
+        weakest = min(dense_frac, key=dense_frac.get)
+        line["dense_roofline"] = {
+            "unit": "fraction of 8 TB/s, algorithmic bytes / HIP-event time of 20 back-to-back launches "
+                    "(median single launch for the evicted-cache row)",
+            "frac": dense_frac,
+            "min_dense_frac": dense_frac[weakest],
+            "min_dense_row": weakest,
+        }
 
     print(json.dumps(line))
 

@@ -170,9 +170,14 @@ mlf_status mlf_apply_grouped(float *model, float *momentum,
  * With n_order == 0 the model is left as it is and the norms describe it.
  *
  * The sums are taken in binary64 (squares of binary32 values are exact there; a
- * difference w_after - w_before is rounded once to binary64), in an order fixed
- * by n and the data type alone, so they are reproducible bit for bit; they agree
- * with the exactly rounded sums to about 1e-14 relative.
+ * difference w_after - w_before is rounded once to binary64) in a fixed order,
+ * so a call repeated with the same arguments on the same device gives the same
+ * bits.  The order depends on n, on the data type of the updates, on whether
+ * every pointer of the call is 16-byte aligned (128-bit or element-wise path),
+ * on whether momentum is given and whether 4n bytes per written vector exceed
+ * 256 MiB in total (these select the tile shape), and on the number of XCDs of
+ * the device; calls that differ in any of these may differ in the last bits.
+ * The sums agree with the exactly rounded ones to about 1e-14 relative.
  *
  *   norm_sq / norms_sq  device, 1 / 2 doubles, 8-byte aligned; written
  *   workspace           device scratch of mlf_norms_workspace_bytes(n) bytes,
@@ -198,8 +203,8 @@ mlf_status mlf_apply_grouped_norms(float *model, float *momentum,
  * Exact server-replica divergence (Sec. 3.3 "Enforcing bounded consistency" and
  * Sec. 5.3: the replica is kept within ||w_s - w_r||_2 <= Div_max of the server).
  *   dist_sq[0] = sum_i (w_server[i] - w_replica[i])^2
- * in binary64, each difference rounded once, summed in an order fixed by n, so
- * reproducible bit for bit.  A replica catches up by applying the updates it
+ * in binary64, each difference rounded once, summed in an order fixed by n and
+ * by whether both vectors are 16-byte aligned, so reproducible bit for bit.  A replica catches up by applying the updates it
  * lags by with mlf_apply_ordered / mlf_apply_grouped in the server's order; the
  * same updates in the same order give the same model bit for bit.
  *
@@ -217,7 +222,7 @@ mlf_status mlf_divergence(const float *w_server, const float *w_replica, int64_t
  * workspace to pass: code running under HIP graph capture, tight serving loops,
  * harnesses that forbid hipMalloc.  Same arguments without the workspace, same
  * kernels, same result bit for bit.  The partial sums go to an array of
- * (MLF_STATIC_MAX_N / 512 + 4162) * 16 bytes (about 8.1 MiB) that is part of the
+ * (MLF_STATIC_MAX_N / 1024 + 4162) * 16 bytes (about 4.1 MiB) that is part of the
  * library's device code: every GPU the library runs on holds one copy until the
  * process ends.  The call allocates and frees nothing; the first call on a
  * device looks up the address of that device's copy (make it outside a graph

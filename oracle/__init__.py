@@ -302,6 +302,21 @@ def scatter_add(counts, totals, V, T, triples, threads=1):
     return int(sum(_run(jobs, threads)))
 
 
+def touched_cells(V, T, triples, threads=1):
+    """Number of distinct cells of the V x T matrix that the valid triples hit:
+    scatter_add of the same triples with every delta replaced by 1 into a zero
+    matrix, then the non-zero cells are counted.  (A measurement for the
+    benchmark's byte count, not part of the method.)"""
+    ones = []
+    for t in triples:
+        u = np.ascontiguousarray(t).copy()
+        u[:, 2] = 1
+        ones.append(u)
+    counts = np.zeros(V * T, dtype=np.int32)
+    scatter_add(counts, None, V, T, ones, threads=threads)
+    return int(np.count_nonzero(counts))
+
+
 def counts_add_dense(counts, totals, V, T, deltas, threads=1):
     """counts += sum of the workers' dense int32 V x T delta matrices, totals +=
     its column sums; in place.  ``deltas`` is a list of int32 arrays of V*T."""

@@ -16,35 +16,16 @@
 // on its own, as the definitions in mlfabric.h state.
 #include <hip/hip_runtime.h>
 
+#include <stddef.h>
 #include <stdint.h>
 
 #include <atomic>
+#include <tuple>
+#include <utility>
 
 #include "mlfabric.h"
 
 #pragma clang fp contract(off)
-
-// Launch shapes: lanes per workgroup, groups per lane and tile, and number of
-// updates whose loads are issued before any is consumed.  They are macros so that
-// a sweep can rebuild the library with other values; the defaults are the best
-// of such sweeps on MI355X (small workgroups, 32 loads in flight per lane).
-#ifndef MLF_SHAPE_F32
-#define MLF_SHAPE_F32 64, 2, 16
-#endif
-#ifndef MLF_SHAPE_BF16V4      // bfloat16, 4 elements per lane and group
-#define MLF_SHAPE_BF16V4 64, 2, 8
-#endif
-#ifndef MLF_SHAPE_NORMS       // variants that also reduce norms (one wavefront per workgroup)
-#define MLF_SHAPE_NORMS 64, 2, 8
-#endif
-#ifndef MLF_SHAPE_BF16V8      // bfloat16, 8 elements per lane and group
-#define MLF_SHAPE_BF16V8 256, 1, 8
-#endif
-// 0: model / momentum use streaming (no-reuse) accesses only when they are too
-// large to stay in the 256 MiB Infinity Cache between calls; 1: never; 4: always.
-#ifndef MLF_STATE_POLICY
-#define MLF_STATE_POLICY 0
-#endif
 
 namespace {
 
@@ -60,6 +41,8 @@ enum Op { kAggregate = 0, kAggregateApply = 1, kApplyOrdered = 2, kApplyGrouped 
 constexpr long long kInfinityCacheBytes = 256ll << 20;
 // Workgroups that walk the element-wise region (they stride over it).
 constexpr long long kMaxScalarGroups = 4096;
+// Elements in the smallest tile of any launch shape (64 lanes x 1 group x 4).
+constexpr long long kMinTileElements = 256;
 
 // Kernel argument block.  The host has already applied the scheduler's order:
 // u[t] / wt[t] belong to the t-th committed update (wt = 1 without weights:
@@ -75,10 +58,33 @@ struct DenseArgs {
     long long n;            // elements
     long long n_vec;        // leading elements on the 128-bit path (0 if unaligned)
     unsigned tiles_vec;     // workgroups [0, tiles_vec) each own one 128-bit tile
+    unsigned xcds;          // XCDs of the device (workgroups go to them in turn)
     int M;                  // committed updates
     float lr;
     float mu;
 };
+
+// The two tables of the argument block are indexed with run-time positions.
+// They are read where the launch put them, in the kernel-argument segment
+// (scalar loads, wavefront-uniform): the argument block is the kernel's only
+// parameter and so starts that segment.  (Indexing the by-value parameter
+// instead makes the compiler copy the whole block to per-lane scratch once the
+// unrolled code refers to it often enough.)
+#define MLF_KERNARG __attribute__((address_space(4)))
+typedef const void *const MLF_KERNARG *UpdateTable;
+typedef const float MLF_KERNARG *WeightTable;
+
+__device__ __forceinline__ UpdateTable kernarg_updates()
+{
+    const char MLF_KERNARG *base = (const char MLF_KERNARG *)__builtin_amdgcn_kernarg_segment_ptr();
+    return reinterpret_cast<UpdateTable>(base + offsetof(DenseArgs, u));
+}
+
+__device__ __forceinline__ WeightTable kernarg_weights()
+{
+    const char MLF_KERNARG *base = (const char MLF_KERNARG *)__builtin_amdgcn_kernarg_segment_ptr();
+    return reinterpret_cast<WeightTable>(base + offsetof(DenseArgs, wt));
+}
 
 struct F32 {
     typedef float elem;
@@ -96,6 +102,50 @@ struct BF16V8 {
 struct BF16V4 {
     typedef uint16_t elem;
     static constexpr int kVec = 4;
+};
+
+// Launch shapes.  A workgroup is one tile: THREADS lanes, each with VPT groups of
+// consecutive elements, THREADS groups apart.  The committed sequence is consumed
+// in blocks of HALF updates through two register buffers: the loads of the next
+// block are issued before the current one is consumed.  WAVES = 1 caps the
+// wavefronts per SIMD at one.  The values are the best of sweeps on MI355X:
+//
+//  - binary32 updates, state streamed (more than the memory-side cache holds):
+//    ONE wavefront per SIMD and the narrowest tile (one 128-bit group per lane,
+//    1 KiB per vector and wavefront).  The fewer and the narrower the tiles in
+//    flight, the shorter the stretch of every vector that the chip works on at
+//    one time, and the cheaper the write-back of model and momentum gets (an
+//    ordered apply of 32 updates of 61 M elements: 6.1-6.2 TB/s against 5.7-5.8
+//    with three wavefronts per SIMD and 2 KiB tiles; the same loads without the
+//    stores run at 7.1 TB/s either way).  Spreading the tiles in flight over 16
+//    distant regions costs 6 %; tiles of 512 bytes per vector lose 10-25 %;
+//  - bfloat16 updates, state streamed: a quarter of the traffic is stores and
+//    64-bit update loads cover only 512 bytes per wavefront, so the wider tile
+//    and the uncapped occupancy are kept (6.4 TB/s; the narrow capped shape
+//    drops to 3.4 TB/s);
+//  - state that stays cached between calls: wider tiles, no cap.
+template <typename IN, bool STREAMED, bool NORMS>
+struct Shape;
+
+template <bool NORMS>
+struct Shape<F32, true, NORMS> {     // streamed state, binary32 updates
+    static constexpr int kThreads = 64, kVpt = 1, kHalf = 8, kWaves = 1;
+};
+template <bool NORMS>
+struct Shape<BF16V4, true, NORMS> {  // streamed state, bfloat16 updates
+    static constexpr int kThreads = 64, kVpt = 2, kHalf = 4, kWaves = 0;
+};
+template <bool NORMS>
+struct Shape<F32, false, NORMS> {    // cached state, binary32 updates
+    static constexpr int kThreads = 64, kVpt = 2, kHalf = 8, kWaves = 0;
+};
+template <>
+struct Shape<BF16V8, false, false> { // cached state, bfloat16 updates
+    static constexpr int kThreads = 256, kVpt = 1, kHalf = 4, kWaves = 0;
+};
+template <>
+struct Shape<BF16V8, false, true> {  // the same with norms: one wavefront per workgroup
+    static constexpr int kThreads = 64, kVpt = 2, kHalf = 4, kWaves = 0;
 };
 
 __device__ __forceinline__ float from_bits(uint32_t b) { return __uint_as_float(b); }
@@ -199,9 +249,11 @@ __device__ __forceinline__ void server_step(float &w, float &h, float g, float l
 //   g0       this lane's first group in that region
 //   n_groups groups in the region
 template <typename IN, int W, int OP, bool HAS_H, int STREAM, bool NORMS, int THREADS, int VPT,
-          int CH, bool FULL>
+          int HALF, bool FULL>
 struct Tile {
     const DenseArgs &a;
+    const UpdateTable u = kernarg_updates();    // a.u and a.wt, see UpdateTable
+    const WeightTable wt_of = kernarg_weights();
     long long e[VPT];       // first element of each group
     bool ok[VPT];
     float acc[VPT][W];      // running sum   (aggregate, aggregate+apply)
@@ -221,15 +273,13 @@ struct Tile {
         }
     }
 
-    // Consume C updates starting at position t0 of the sequence: all loads
-    // first (memory-level parallelism), then the arithmetic in sequence order.
+    // Issues the loads of the C updates at positions t0 .. t0 + C - 1.
     template <int C>
-    __device__ __forceinline__ void chunk(int t0)
+    __device__ __forceinline__ void fetch(float (&x)[C][VPT][W], int t0)
     {
-        float x[C][VPT][W];
 #pragma unroll
         for (int c = 0; c < C; ++c) {
-            const void *p = a.u[t0 + c];
+            const void *p = u[t0 + c];
 #pragma unroll
             for (int v = 0; v < VPT; ++v) {
                 if (ok[v]) {
@@ -240,9 +290,16 @@ struct Tile {
                 }
             }
         }
+    }
+
+    // The arithmetic for the C updates at positions t0 .. t0 + C - 1, in
+    // sequence order.
+    template <int C>
+    __device__ __forceinline__ void consume(const float (&x)[C][VPT][W], int t0)
+    {
 #pragma unroll
         for (int c = 0; c < C; ++c) {
-            const float wt = a.wt[t0 + c];
+            const float wt = wt_of[t0 + c];
             const bool first = (c == 0) && (t0 == 0);
             // Grouped apply: a position opens a group when its predecessor closed
             // one; uniform over the wavefront (scalar tests of the bit mask).
@@ -269,13 +326,16 @@ struct Tile {
         }
     }
 
-    // Remainder of the sequence in halving pieces; positions stay in order.
+    // What is left of the sequence after the whole blocks, in halving pieces
+    // (loaded, then consumed); positions stay in order.
     template <int C>
     __device__ __forceinline__ void remainder(int &t)
     {
         if constexpr (C >= 1) {
             if (a.M - t >= C) {
-                chunk<C>(t);
+                float x[C][VPT][W];
+                fetch<C>(x, t);
+                consume<C>(x, t);
                 t += C;
             }
             remainder<C / 2>(t);
@@ -308,9 +368,33 @@ struct Tile {
             }
         }
 
+        // Whole blocks of HALF updates alternate between two register buffers:
+        // a block's loads are in flight while the block before it is consumed.
+        const int M = a.M;
         int t = 0;
-        for (; t + CH <= a.M; t += CH) chunk<CH>(t);
-        remainder<CH / 2>(t);
+        if (M >= HALF) {
+            float x0[HALF][VPT][W], x1[HALF][VPT][W];
+            fetch<HALF>(x0, 0);
+            for (;;) {
+                if (t + 2 * HALF > M) {
+                    consume<HALF>(x0, t);
+                    t += HALF;
+                    break;
+                }
+                fetch<HALF>(x1, t + HALF);
+                consume<HALF>(x0, t);
+                t += HALF;
+                if (t + 2 * HALF > M) {
+                    consume<HALF>(x1, t);
+                    t += HALF;
+                    break;
+                }
+                fetch<HALF>(x0, t + HALF);
+                consume<HALF>(x1, t);
+                t += HALF;
+            }
+        }
+        remainder<HALF / 2>(t);
 
 #pragma unroll
         for (int v = 0; v < VPT; ++v) {
@@ -346,27 +430,25 @@ struct Tile {
     }
 };
 
-// Workgroups are handed to the 8 XCDs (each with its own L2) in turn.  With
-// RUN > 0 every XCD takes runs of RUN consecutive tiles instead of every eighth
-// tile, so that the lines an L2 writes back lie together; the last, incomplete
-// block of 8 * RUN workgroups keeps the plain numbering, which keeps the map
-// one to one.  Used where model and momentum go through the caches (+5 % there;
-// no gain, or a loss, where they are streamed).
-#ifndef MLF_XCD_RUN
-#define MLF_XCD_RUN 512
-#endif
+// Workgroups are handed to the XCDs (each with its own L2) in turn.  With
+// RUN > 0 every XCD takes runs of RUN consecutive tiles instead of every
+// xcds-th tile, so that the lines an L2 writes back lie together; the last,
+// incomplete block of xcds * RUN workgroups keeps the plain numbering, which
+// keeps the map one to one.  Used where model and momentum go through the
+// caches (+1 to 5 % there; no gain, or a loss, where they are streamed).
+constexpr unsigned kXcdRun = 512;
 
 template <unsigned RUN>
-__device__ __forceinline__ long long xcd_tile(unsigned block, unsigned tiles)
+__device__ __forceinline__ long long xcd_tile(unsigned block, unsigned tiles, unsigned xcds)
 {
     if constexpr (RUN == 0) {
         return block;
     } else {
-        constexpr unsigned kBlock = 8 * RUN;
-        const unsigned first = block / kBlock * kBlock;
-        if (first + kBlock > tiles) return block;
+        const unsigned per_block = xcds * RUN;
+        const unsigned first = block / per_block * per_block;
+        if (first + per_block > tiles) return block;
         const unsigned r = block - first;
-        return first + (r % 8) * RUN + r / 8;
+        return first + (r % xcds) * RUN + r / xcds;
     }
 }
 
@@ -375,8 +457,9 @@ __device__ __forceinline__ long long xcd_tile(unsigned block, unsigned tiles)
 // [n_vec, n): the ragged tail, or everything when a pointer of the call is not
 // 16-byte aligned.  Norms variants (one wavefront per workgroup) end with a
 // shuffle reduction in a fixed order and one pair of partial sums per workgroup.
-template <typename IN, int OP, bool HAS_H, int STREAM, bool NORMS, int THREADS, int VPT, int CH>
-__global__ __launch_bounds__(THREADS) void dense_kernel(const DenseArgs a)
+template <typename IN, int OP, bool HAS_H, int STREAM, bool NORMS, int THREADS, int VPT, int HALF,
+          int WAVES>
+__device__ __forceinline__ void dense_body(const DenseArgs &a)
 {
     static_assert(!NORMS || THREADS == 64, "norms are reduced within one wavefront");
     constexpr int WV = IN::kVec;
@@ -384,18 +467,18 @@ __global__ __launch_bounds__(THREADS) void dense_kernel(const DenseArgs a)
     double sums[2] = {0.0, 0.0};
     if (blockIdx.x < a.tiles_vec) {
         const long long groups = a.n_vec / WV;
-        constexpr unsigned kRun = (STREAM == 0 && OP != kAggregate) ? MLF_XCD_RUN : 0;
-        const long long base = xcd_tile<kRun>(blockIdx.x, a.tiles_vec) * kTile;
+        constexpr unsigned kRun = (STREAM == 0 && OP != kAggregate) ? kXcdRun : 0;
+        const long long base = xcd_tile<kRun>(blockIdx.x, a.tiles_vec, a.xcds) * kTile;
         if (base + kTile <= groups) {
-            Tile<IN, WV, OP, HAS_H, STREAM, NORMS, THREADS, VPT, CH, true>(a, 0, base + threadIdx.x, groups).run(sums);
+            Tile<IN, WV, OP, HAS_H, STREAM, NORMS, THREADS, VPT, HALF, true>(a, 0, base + threadIdx.x, groups).run(sums);
         } else {
-            Tile<IN, WV, OP, HAS_H, STREAM, NORMS, THREADS, VPT, CH, false>(a, 0, base + threadIdx.x, groups).run(sums);
+            Tile<IN, WV, OP, HAS_H, STREAM, NORMS, THREADS, VPT, HALF, false>(a, 0, base + threadIdx.x, groups).run(sums);
         }
     } else {
         const long long groups = a.n - a.n_vec;
         const long long stride = static_cast<long long>(gridDim.x - a.tiles_vec) * kTile;
         for (long long base = (blockIdx.x - a.tiles_vec) * kTile; base < groups; base += stride) {
-            Tile<IN, 1, OP, HAS_H, STREAM, NORMS, THREADS, VPT, CH, false>(a, a.n_vec, base + threadIdx.x, groups).run(sums);
+            Tile<IN, 1, OP, HAS_H, STREAM, NORMS, THREADS, VPT, HALF, false>(a, a.n_vec, base + threadIdx.x, groups).run(sums);
         }
     }
     if constexpr (NORMS) {
@@ -409,6 +492,22 @@ __global__ __launch_bounds__(THREADS) void dense_kernel(const DenseArgs a)
             a.partials[2 * static_cast<size_t>(blockIdx.x) + 1] = s1;
         }
     }
+}
+
+// The kernel proper.  WAVES > 0 caps the wavefronts per SIMD at WAVES (the
+// register allocation is raised to match, so the hardware cannot place more).
+template <typename IN, int OP, bool HAS_H, int STREAM, bool NORMS, int THREADS, int VPT, int HALF,
+          int WAVES>
+__global__ __launch_bounds__(THREADS) void dense_kernel(const DenseArgs a)
+{
+    dense_body<IN, OP, HAS_H, STREAM, NORMS, THREADS, VPT, HALF, WAVES>(a);
+}
+
+template <typename IN, int OP, bool HAS_H, int STREAM, bool NORMS, int THREADS, int VPT, int HALF>
+__global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(1, 1)))
+void dense_kernel_one_wave(const DenseArgs a)
+{
+    dense_body<IN, OP, HAS_H, STREAM, NORMS, THREADS, VPT, HALF, 1>(a);
 }
 
 // Sums pairs of partial sums in a fixed order, so that the norms of a call are
@@ -462,25 +561,46 @@ __global__ __launch_bounds__(kFinishThreads) void norms_finish_kernel(const doub
     }
 }
 
+// Launches `kernel` and returns the status of this launch itself, so that a
+// sticky error left by an earlier, unrelated HIP call is not mistaken for a
+// failure here.  The arguments are converted to the kernel's parameter types.
+template <typename... PARAMS, size_t... I>
+bool launch_with(void (*kernel)(PARAMS...), dim3 grid, dim3 block, size_t lds, hipStream_t stream,
+                 std::tuple<PARAMS...> &values, std::index_sequence<I...>)
+{
+    void *params[] = {static_cast<void *>(&std::get<I>(values))...};
+    return hipLaunchKernel(reinterpret_cast<const void *>(kernel), grid, block, params, lds, stream) ==
+           hipSuccess;
+}
+
+template <typename... PARAMS, typename... ARGS>
+bool launch_kernel(void (*kernel)(PARAMS...), dim3 grid, dim3 block, size_t lds, hipStream_t stream,
+                   ARGS &&...args)
+{
+    static_assert(sizeof...(PARAMS) == sizeof...(ARGS), "one argument per kernel parameter");
+    std::tuple<PARAMS...> values{static_cast<PARAMS>(args)...};
+    return launch_with(kernel, grid, block, lds, stream, values, std::index_sequence_for<PARAMS...>{});
+}
+
 // Launches the reduction of `n_partials` pairs at `partials` into out[0..n_out).
 // The kFinishSlices pairs after the capacity of the list are the scratch of the
 // two-stage form.
 bool finish_norms(double *partials, unsigned n_partials, size_t capacity, double *out, int n_out,
                   hipStream_t stream)
 {
+    const double *in = partials;
     if (n_partials >= kFinishTwoStageMin) {
         double *slices = partials + 2 * capacity;
         const unsigned slice = (n_partials + kFinishSlices - 1) / kFinishSlices;
-        norms_finish_kernel<<<dim3(kFinishSlices), dim3(kFinishThreads), 0, stream>>>(
-            partials, n_partials, slice, slices, 2);
-        if (hipGetLastError() != hipSuccess) return false;
-        norms_finish_kernel<<<dim3(1), dim3(kFinishThreads), 0, stream>>>(
-            slices, kFinishSlices, kFinishSlices, out, n_out);
-    } else {
-        norms_finish_kernel<<<dim3(1), dim3(kFinishThreads), 0, stream>>>(
-            partials, n_partials, n_partials, out, n_out);
+        if (!launch_kernel(norms_finish_kernel, dim3(kFinishSlices), dim3(kFinishThreads), 0, stream, in,
+                           n_partials, slice, slices, 2)) {
+            return false;
+        }
+        in = slices;
+        n_partials = kFinishSlices;
     }
-    return hipGetLastError() == hipSuccess;
+    return launch_kernel(norms_finish_kernel, dim3(1), dim3(kFinishThreads), 0, stream, in, n_partials,
+                         n_partials, out, n_out);
 }
 
 // Exact server-replica divergence (Sec. 3.3 / 5.3: bounded consistency keeps
@@ -546,6 +666,23 @@ Range range_of(const void *p, long long n, size_t elem)
     return Range{lo, lo + static_cast<uintptr_t>(n) * elem};
 }
 
+// XCDs of the current device (its workgroups are handed to them in turn);
+// looked up once per device.  1 when the runtime cannot tell: tile numbering
+// then stays plain.
+unsigned xcd_count()
+{
+    constexpr int kMaxDevices = 64;
+    static std::atomic<int> cached[kMaxDevices];
+    int device = 0;
+    if (hipGetDevice(&device) != hipSuccess || device < 0 || device >= kMaxDevices) return 1;
+    int n = cached[device].load(std::memory_order_relaxed);
+    if (n == 0) {
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeNumberOfXccs, device) != hipSuccess || n < 1) n = 1;
+        cached[device].store(n, std::memory_order_relaxed);
+    }
+    return static_cast<unsigned>(n);
+}
+
 // Workgroups a launch of this shape uses (tiles of the 128-bit region plus the
 // workgroups of the element-wise region).
 template <typename IN, int THREADS, int VPT>
@@ -558,21 +695,30 @@ void count_workgroups(const DenseArgs &a, long long &n_vec, long long &tiles_v, 
     if (tiles_s > kMaxScalarGroups) tiles_s = kMaxScalarGroups;
 }
 
-template <typename IN, int OP, bool HAS_H, int STREAM, bool NORMS, int THREADS, int VPT, int CH>
-mlf_status launch_shape(DenseArgs &a, hipStream_t stream, double *norms_out,
-                        size_t partials_capacity)
+template <typename IN, int OP, bool HAS_H, int STREAM, bool NORMS>
+mlf_status launch(DenseArgs &a, hipStream_t stream, double *norms_out, size_t partials_capacity)
 {
+    typedef Shape<IN, STREAM != 0, NORMS> S;
+    static_assert(S::kWaves == 0 || S::kWaves == 1, "the cap is one wavefront per SIMD, or none");
+    static_assert(64 * S::kVpt * IN::kVec >= kMinTileElements || !NORMS, "a norms tile yields one partial pair");
     long long n_vec, tiles_v, tiles_s;
-    count_workgroups<IN, THREADS, VPT>(a, n_vec, tiles_v, tiles_s);
+    count_workgroups<IN, S::kThreads, S::kVpt>(a, n_vec, tiles_v, tiles_s);
     if (tiles_v + tiles_s > 0x7fffffffll) return MLF_EUNSUPPORTED;
     if (NORMS && static_cast<size_t>(tiles_v + tiles_s) > partials_capacity) return MLF_EINVAL;
     a.n_vec = n_vec;
     a.tiles_vec = static_cast<unsigned>(tiles_v);
+    a.xcds = xcd_count();
     const unsigned grid = static_cast<unsigned>(tiles_v + tiles_s);
     if (grid > 0) {
-        dense_kernel<IN, OP, HAS_H, STREAM, NORMS, THREADS, VPT, CH>
-            <<<dim3(grid), dim3(THREADS), 0, stream>>>(a);
-        if (hipGetLastError() != hipSuccess) return MLF_EHIP;
+        bool ok;
+        if constexpr (S::kWaves == 1) {
+            ok = launch_kernel(dense_kernel_one_wave<IN, OP, HAS_H, STREAM, NORMS, S::kThreads, S::kVpt, S::kHalf>,
+                               dim3(grid), dim3(S::kThreads), 0, stream, a);
+        } else {
+            ok = launch_kernel(dense_kernel<IN, OP, HAS_H, STREAM, NORMS, S::kThreads, S::kVpt, S::kHalf, 0>,
+                               dim3(grid), dim3(S::kThreads), 0, stream, a);
+        }
+        if (!ok) return MLF_EHIP;
     }
     if constexpr (NORMS) {
         if (!finish_norms(a.partials, grid, partials_capacity, norms_out, OP == kAggregate ? 1 : 2, stream)) {
@@ -580,21 +726,6 @@ mlf_status launch_shape(DenseArgs &a, hipStream_t stream, double *norms_out,
         }
     }
     return MLF_OK;
-}
-
-template <typename IN, int OP, bool HAS_H, int STREAM, bool NORMS>
-mlf_status launch(DenseArgs &a, hipStream_t stream, double *norms_out, size_t partials_capacity)
-{
-    if constexpr (NORMS) {
-        return launch_shape<IN, OP, HAS_H, STREAM, true, MLF_SHAPE_NORMS>(a, stream, norms_out,
-                                                                          partials_capacity);
-    } else if constexpr (sizeof(typename IN::elem) == 4) {
-        return launch_shape<IN, OP, HAS_H, STREAM, false, MLF_SHAPE_F32>(a, stream, nullptr, 0);
-    } else if constexpr (IN::kVec == 4) {
-        return launch_shape<IN, OP, HAS_H, STREAM, false, MLF_SHAPE_BF16V4>(a, stream, nullptr, 0);
-    } else {
-        return launch_shape<IN, OP, HAS_H, STREAM, false, MLF_SHAPE_BF16V8>(a, stream, nullptr, 0);
-    }
 }
 
 template <typename IN, int OP, int STREAM, bool NORMS>
@@ -613,21 +744,20 @@ template <int OP, bool NORMS = false>
 mlf_status dispatch(DenseArgs &a, mlf_dtype dtype, hipStream_t stream, double *norms_out = nullptr,
                     size_t capacity = 0)
 {
-    // State that is too large to survive in the Infinity Cache until the next
-    // call is streamed through; smaller state is left cacheable.  The output of
-    // a plain aggregate is never read back by this library: always streamed.
+    // State that is too large to survive in the memory-side cache until the
+    // next call is streamed through (no-reuse hint on its loads and stores);
+    // smaller state is left cacheable.  The output of a plain aggregate is
+    // never read back by this library: always streamed.
     long long footprint = 0;
     if (a.model != nullptr) footprint += 4 * a.n;
     if (a.momentum != nullptr) footprint += 4 * a.n;
     if (a.out != nullptr) footprint += 4 * a.n;
-    constexpr int kS = MLF_STATE_POLICY >= 2 ? MLF_STATE_POLICY - 1 : 3;
-    const bool streaming = MLF_STATE_POLICY >= 2 ||
-                           (MLF_STATE_POLICY == 0 && (OP == kAggregate || footprint > kInfinityCacheBytes));
+    const bool streaming = OP == kAggregate || footprint > kInfinityCacheBytes;
     if (dtype == MLF_F32) {
-        return streaming ? dispatch_state<F32, OP, kS, NORMS>(a, stream, norms_out, capacity)
+        return streaming ? dispatch_state<F32, OP, 3, NORMS>(a, stream, norms_out, capacity)
                          : dispatch_state<F32, OP, 0, NORMS>(a, stream, norms_out, capacity);
     }
-    return streaming ? dispatch_state<BF16V4, OP, kS, NORMS>(a, stream, norms_out, capacity)
+    return streaming ? dispatch_state<BF16V4, OP, 3, NORMS>(a, stream, norms_out, capacity)
                      : dispatch_state<BF16V8, OP, 0, NORMS>(a, stream, norms_out, capacity);
 }
 
@@ -782,11 +912,17 @@ extern "C" mlf_status mlf_apply_grouped(float *model, float *momentum,
     return dispatch<kApplyGrouped>(a, dtype, static_cast<hipStream_t>(stream));
 }
 
-// Partial sums a norms variant may need: one pair per workgroup of the
-// (64 lanes x 2 groups) shape, for either layout of the elements.
+// Partial sums a norms variant may need: one pair per workgroup, and the
+// smallest tile of any shape holds kMinTileElements elements.
 static constexpr size_t norms_partials_capacity(long long n)
 {
-    return static_cast<size_t>(n / (64 * 2 * 4)) + 2 + static_cast<size_t>(kMaxScalarGroups);
+    return static_cast<size_t>(n / kMinTileElements) + 2 + static_cast<size_t>(kMaxScalarGroups);
+}
+
+// The same for the divergence kernel alone (tiles of 64 * kDivUnroll groups).
+static constexpr size_t divergence_partials_capacity(long long n)
+{
+    return static_cast<size_t>(n / (64 * kDivUnroll * 4)) + 2 + static_cast<size_t>(kMaxScalarGroups);
 }
 
 extern "C" size_t mlf_norms_workspace_bytes(int64_t n)
@@ -847,10 +983,12 @@ extern "C" mlf_status mlf_apply_grouped_norms(float *model, float *momentum,
 }
 
 // Squared distance of two vectors with the partial sums in `partials` (room for
-// norms_partials_capacity(n) + kFinishSlices pairs).  Every partial that is read
-// has been written by this call, so the buffer needs no clearing.
+// capacity + kFinishSlices pairs, capacity >= divergence_partials_capacity(n)).
+// Every partial that is read has been written by this call, so the buffer needs
+// no clearing.
 static mlf_status divergence_launch(const float *w_server, const float *w_replica, long long n,
-                                    double *dist_sq, double *partials, hipStream_t s)
+                                    double *dist_sq, double *partials, size_t capacity,
+                                    hipStream_t s)
 {
     const bool aligned16 = reinterpret_cast<uintptr_t>(w_server) % 16 == 0 &&
                            reinterpret_cast<uintptr_t>(w_replica) % 16 == 0;
@@ -859,14 +997,15 @@ static mlf_status divergence_launch(const float *w_server, const float *w_replic
     const long long tiles_v = (n_vec / 4 + per_tile - 1) / per_tile;
     long long tiles_s = (n - n_vec + 63) / 64;
     if (tiles_s > kMaxScalarGroups) tiles_s = kMaxScalarGroups;
-    if (static_cast<size_t>(tiles_v + tiles_s) > norms_partials_capacity(n)) return MLF_EUNSUPPORTED;
+    if (static_cast<size_t>(tiles_v + tiles_s) > capacity) return MLF_EUNSUPPORTED;
     const unsigned grid = static_cast<unsigned>(tiles_v + tiles_s);
     if (grid > 0) {
-        divergence_kernel<<<dim3(grid), dim3(64), 0, s>>>(w_server, w_replica, n, n_vec,
-                                                         static_cast<unsigned>(tiles_v), partials);
-        if (hipGetLastError() != hipSuccess) return MLF_EHIP;
+        if (!launch_kernel(divergence_kernel, dim3(grid), dim3(64), 0, s, w_server, w_replica, n, n_vec,
+                           static_cast<unsigned>(tiles_v), partials)) {
+            return MLF_EHIP;
+        }
     }
-    return finish_norms(partials, grid, norms_partials_capacity(n), dist_sq, 1, s) ? MLF_OK : MLF_EHIP;
+    return finish_norms(partials, grid, capacity, dist_sq, 1, s) ? MLF_OK : MLF_EHIP;
 }
 
 static mlf_status divergence_check(const float *w_server, const float *w_replica, long long n,
@@ -890,7 +1029,7 @@ extern "C" mlf_status mlf_divergence(const float *w_server, const float *w_repli
     const mlf_status st = divergence_check(w_server, w_replica, n, dist_sq);
     if (st != MLF_OK) return st;
     return divergence_launch(w_server, w_replica, n, dist_sq, static_cast<double *>(workspace),
-                             static_cast<hipStream_t>(stream));
+                             norms_partials_capacity(n), static_cast<hipStream_t>(stream));
 }
 
 // ---------------------------------------------------------------------------
@@ -901,7 +1040,7 @@ extern "C" mlf_status mlf_divergence(const float *w_server, const float *w_repli
 // name is only ever used in that lookup: host code passes the looked-up pointer.
 // ---------------------------------------------------------------------------
 constexpr size_t kStaticScratchBytes =
-    (norms_partials_capacity(MLF_STATIC_MAX_N) + kFinishSlices) * 2 * sizeof(double);
+    (divergence_partials_capacity(MLF_STATIC_MAX_N) + kFinishSlices) * 2 * sizeof(double);
 static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 constexpr int kMaxDevices = 64;
@@ -937,7 +1076,7 @@ extern "C" mlf_status mlf_divergence_static(const float *w_server, const float *
     const mlf_status found = static_scratch(&partials);
     if (found != MLF_OK) return found;
     return divergence_launch(w_server, w_replica, n, dist_sq, partials,
-                             static_cast<hipStream_t>(stream));
+                             divergence_partials_capacity(MLF_STATIC_MAX_N), static_cast<hipStream_t>(stream));
 }
 
 extern "C" const char *mlf_status_string(mlf_status status)

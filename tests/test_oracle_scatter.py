@@ -167,3 +167,20 @@ def test_dense_delta_sum_against_numpy_and_wraparound():
     c = np.array([1, 2], dtype=np.int32)
     oracle.counts_add_dense(c, None, 2, 1, [])             # no workers, no totals
     assert c.tolist() == [1, 2]
+
+
+def test_touched_cells_counts_distinct_valid_cells():
+    """Pinned by numpy.unique on the flat indices of the valid triples; deltas that
+    cancel and triples that repeat a cell must not change the count."""
+    rng = np.random.default_rng(5)
+    V, T = 37, 11
+    tr = np.stack([rng.integers(-2, V + 2, 4000), rng.integers(-1, T + 1, 4000),
+                   rng.choice([-1, 1], 4000)], axis=1).astype(np.int32)
+    valid = (tr[:, 0] >= 0) & (tr[:, 0] < V) & (tr[:, 1] >= 0) & (tr[:, 1] < T)
+    want = np.unique(tr[valid, 0].astype(np.int64) * T + tr[valid, 1]).size
+    halves = [tr[:1500].copy(), tr[1500:].copy()]
+    assert oracle.touched_cells(V, T, halves) == want
+    assert oracle.touched_cells(V, T, halves, threads=4) == want
+    cancel = np.array([[3, 2, 1], [3, 2, -1], [3, 2, 5]], dtype=np.int32)
+    assert oracle.touched_cells(V, T, [cancel]) == 1
+    assert oracle.touched_cells(V, T, []) == 0

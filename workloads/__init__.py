@@ -65,11 +65,12 @@ class SparseConfig:
     def seed(self) -> int:
         return BASE_SEED + self.index
 
-    def algorithmic_bytes(self, m=None) -> int:
-        """12 bytes of triple stream plus one 4-byte read-modify-write of the
-        count cell per triple (totals stay on chip)."""
+    def algorithmic_bytes(self, distinct_cells: int, m=None) -> int:
+        """12 bytes of triple stream per triple, one 4-byte read and one 4-byte
+        write of every DISTINCT cell the batch touches (counted on the inputs by
+        the caller), and the totals read and written once."""
         m = self.m if m is None else m
-        return (12 + 8) * self.K * m
+        return 12 * self.K * m + 8 * distinct_cells + 8 * self.T
 
 
 CONFIGS = {
