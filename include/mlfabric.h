@@ -262,7 +262,15 @@ mlf_status mlf_divergence_static(const float *w_server, const float *w_replica, 
  *                        aligned, contents undefined before and after.  With it
  *                        the triples are first grouped by the 128 KiB tile of
  *                        counts[] they hit (several times faster for large
- *                        batches); with NULL (or fewer bytes, or a shape that
+ *                        batches); the groups are laid out from a sample of the
+ *                        triples (of every buffer, every p-th block of 256
+ *                        consecutive triples, p = total / (256 * tiles) kept
+ *                        within [1, 64], tiles = ceil(V*T / 32768)), and a
+ *                        triple that finds its group full is added directly,
+ *                        so the result never depends on the sample; a batch
+ *                        whose sampled blocks say nothing about the others
+ *                        runs at the direct path's speed.  With NULL (or fewer
+ *                        bytes, or a shape that
  *                        path does not serve) the call takes the direct path,
  *                        which needs none and gives the same result
  *   n_rejected    device int32 counter that the call ADDS to (the caller clears
@@ -280,7 +288,7 @@ mlf_status mlf_sparse_scatter_add(int32_t *counts, int32_t *totals, int32_t V,
                                   int32_t *n_rejected, mlf_stream stream);
 
 /* Scratch the grouped path of mlf_sparse_scatter_add needs for this problem
- * size: about 16 bytes per triple.  0 when that path would not be used: a
+ * size: 8 to 14 bytes per triple.  0 when that path would not be used: a
  * matrix of more than 2^30 cells, or a batch so small that the direct path is
  * faster (fewer than 262,144 + 600 per 32,768 cells of the matrix triples). */
 size_t mlf_sparse_workspace_bytes(int32_t V, int32_t T, int64_t total_triples);

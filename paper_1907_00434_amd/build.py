@@ -9,6 +9,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmlfabric_hip.so")
 SOURCES = ["dense.hip", "sparse.hip"]
+HEADERS = ["launch.h"]
 
 # -ffp-contract=off: every product and sum is rounded on its own (the results
 # are defined bit for bit).  Packed-FP32 instructions are switched off.
@@ -29,7 +30,7 @@ def hipcc() -> str:
 def build(extra_flags=(), output: str = LIB, verbose: bool = False) -> str:
     """Compile every kernel source into one shared library; returns its path."""
     cmd = [hipcc(), *HIPCC_FLAGS, *extra_flags,
-           "-I", os.path.join(ROOT, "include"),
+           "-I", os.path.join(ROOT, "include"), "-I", CSRC,
            *[os.path.join(CSRC, s) for s in SOURCES], "-o", output]
     if verbose:
         print(" ".join(cmd))
@@ -43,9 +44,29 @@ def build(extra_flags=(), output: str = LIB, verbose: bool = False) -> str:
     return output
 
 
+C_CALLER_SRC = os.path.join(ROOT, "tests", "native", "abi_call_cost.c")
+C_CALLER = os.path.join(ROOT, "tests", "native", "abi_call_cost")
+
+
+def build_c_caller() -> str:
+    """Compile the plain C program that times the bare C ABI (gcc, linked
+    against the built library and the HIP runtime); returns its path."""
+    rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
+    cmd = ["gcc", "-O2", "-std=c11", "-D_POSIX_C_SOURCE=199309L", "-Wall",
+           "-I", os.path.join(ROOT, "include"), "-I", os.path.join(rocm, "include"), C_CALLER_SRC,
+           "-L", HERE, "-lmlfabric_hip", "-L", os.path.join(rocm, "lib"), "-lamdhip64",
+           "-Wl,-rpath,$ORIGIN/../../paper_1907_00434_amd", "-Wl,-rpath," + os.path.join(rocm, "lib"),
+           "-o", C_CALLER]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError(f"gcc failed:\n{res.stderr}")
+    return C_CALLER
+
+
 def is_built() -> bool:
     return os.path.exists(LIB)
 
 
 if __name__ == "__main__":
     print(build(verbose=True))
+    print(build_c_caller())

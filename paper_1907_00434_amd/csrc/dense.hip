@@ -20,9 +20,8 @@
 #include <stdint.h>
 
 #include <atomic>
-#include <tuple>
-#include <utility>
 
+#include "launch.h"
 #include "mlfabric.h"
 
 #pragma clang fp contract(off)
@@ -559,27 +558,6 @@ __global__ __launch_bounds__(kFinishThreads) void norms_finish_kernel(const doub
         out[2 * static_cast<size_t>(blockIdx.x)] = tree[0][0];
         if (n_out > 1) out[2 * static_cast<size_t>(blockIdx.x) + 1] = tree[1][0];
     }
-}
-
-// Launches `kernel` and returns the status of this launch itself, so that a
-// sticky error left by an earlier, unrelated HIP call is not mistaken for a
-// failure here.  The arguments are converted to the kernel's parameter types.
-template <typename... PARAMS, size_t... I>
-bool launch_with(void (*kernel)(PARAMS...), dim3 grid, dim3 block, size_t lds, hipStream_t stream,
-                 std::tuple<PARAMS...> &values, std::index_sequence<I...>)
-{
-    void *params[] = {static_cast<void *>(&std::get<I>(values))...};
-    return hipLaunchKernel(reinterpret_cast<const void *>(kernel), grid, block, params, lds, stream) ==
-           hipSuccess;
-}
-
-template <typename... PARAMS, typename... ARGS>
-bool launch_kernel(void (*kernel)(PARAMS...), dim3 grid, dim3 block, size_t lds, hipStream_t stream,
-                   ARGS &&...args)
-{
-    static_assert(sizeof...(PARAMS) == sizeof...(ARGS), "one argument per kernel parameter");
-    std::tuple<PARAMS...> values{static_cast<PARAMS>(args)...};
-    return launch_with(kernel, grid, block, lds, stream, values, std::index_sequence_for<PARAMS...>{});
 }
 
 // Launches the reduction of `n_partials` pairs at `partials` into out[0..n_out).

@@ -1,0 +1,38 @@
+// Kernel launch helper shared by the kernel sources of the library.
+#ifndef MLF_LAUNCH_H
+#define MLF_LAUNCH_H
+
+#include <hip/hip_runtime.h>
+
+#include <stddef.h>
+
+#include <tuple>
+#include <utility>
+
+namespace mlf_detail {
+
+template <typename... PARAMS, size_t... I>
+bool launch_with(void (*kernel)(PARAMS...), dim3 grid, dim3 block, size_t lds, hipStream_t stream,
+                 std::tuple<PARAMS...> &values, std::index_sequence<I...>)
+{
+    void *params[] = {static_cast<void *>(&std::get<I>(values))...};
+    return hipLaunchKernel(reinterpret_cast<const void *>(kernel), grid, block, params, lds, stream) ==
+           hipSuccess;
+}
+
+}  // namespace mlf_detail
+
+// Launches `kernel` and returns the status of this launch itself, so that a
+// sticky error left by an earlier, unrelated HIP call is not mistaken for a
+// failure here.  The arguments are converted to the kernel's parameter types.
+template <typename... PARAMS, typename... ARGS>
+bool launch_kernel(void (*kernel)(PARAMS...), dim3 grid, dim3 block, size_t lds, hipStream_t stream,
+                   ARGS &&...args)
+{
+    static_assert(sizeof...(PARAMS) == sizeof...(ARGS), "one argument per kernel parameter");
+    std::tuple<PARAMS...> values{static_cast<PARAMS>(args)...};
+    return mlf_detail::launch_with(kernel, grid, block, lds, stream, values,
+                                   std::index_sequence_for<PARAMS...>{});
+}
+
+#endif  // MLF_LAUNCH_H

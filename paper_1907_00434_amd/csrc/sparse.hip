@@ -10,16 +10,23 @@
 // per second, whatever their locality, so this path costs one such operation
 // per triple.
 //
-// Binned path (needs scratch).  Triples are first grouped by the 128 KiB tile
-// of counts[] they fall into (a two-level counting sort: 128 fine tiles per
-// coarse range, so that every partition step writes contiguous runs; the
-// heaviest tiles get a digit of their own at the coarse level and skip the fine
-// one).  One workgroup then owns a tile at a time: it accumulates the tile's records
-// with LDS atomics into a private 32768-cell image and merges the image into
-// counts[] with contiguous 128-bit read-modify-writes (or contiguous atomics
-// when a heavy tile is shared by several workgroups).  Global atomic traffic
-// drops from one operation per triple to one per touched cache line per
-// workgroup, and everything else is streaming.
+// Binned path (needs scratch).  The triples cross HBM once.  They are grouped
+// by the 128 KiB tile of counts[] they fall into (a two-level partition: 128
+// fine tiles per coarse range, so that every partition step writes contiguous
+// runs; the heaviest tiles get a digit of their own at the coarse level and skip
+// the fine one).  Where the groups go is planned from a SAMPLE of the triples
+// (every 64th block of 256, or denser for matrices of many tiles): every tile
+// gets room for its estimated share plus five standard deviations.  A record
+// that finds its group full is added to counts[] with a global atomic on the
+// spot instead, so the result does not depend on how good the estimate was;
+// only the speed does (a batch whose sample says nothing about the rest
+// degrades to the direct path's cost).  One workgroup then owns a tile at a
+// time: it accumulates the tile's records with LDS atomics into a private
+// 32768-cell image and merges the image into counts[] with contiguous 128-bit
+// read-modify-writes (or contiguous atomics when a heavy tile is shared by
+// several workgroups).  Global atomic traffic drops from one operation per
+// triple to one per touched cache line per workgroup, and everything else is
+// streaming.
 //
 // In both paths the T-entry totals vector, which every triple hits, is kept in
 // LDS per workgroup and merged into totals[] once at the end.
@@ -27,63 +34,48 @@
 
 #include <stdint.h>
 
+#include "launch.h"
 #include "mlfabric.h"
 
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kMaxLdsTopics = 16384;     // totals privatised in LDS up to 64 KiB
+constexpr int kMaxLdsTopics = 16384;     // direct path: totals privatised in LDS up to 64 KiB
 
-// ---- geometry of the binned path -------------------------------------------
-#ifndef MLF_TILE_BITS
-#define MLF_TILE_BITS 15
-#endif
-#ifndef MLF_FINE_BITS
-#define MLF_FINE_BITS 7
-#endif
-#ifndef MLF_ACC_THREADS
-#define MLF_ACC_THREADS 1024
-#endif
-#ifndef MLF_ACC_CHUNK_BITS
-#define MLF_ACC_CHUNK_BITS 18
-#endif
-constexpr int kTileBits = MLF_TILE_BITS;         // log2 of the cells per LDS image
+// ---- geometry of the binned path (frozen results of sweeps on MI355X) ---------
+constexpr int kTileBits = 15;                    // log2 of the cells per LDS image (128 KiB)
 constexpr uint32_t kTileCells = 1u << kTileBits;
-constexpr int kFineBits = MLF_FINE_BITS;         // log2 of the fine tiles per coarse range
+constexpr int kFineBits = 7;                     // log2 of the fine tiles per coarse range
 constexpr uint32_t kFinePerCoarse = 1u << kFineBits;
-constexpr uint32_t kMaxCoarse = 256;             // coarse ranges (one counter per lane)
+constexpr uint32_t kMaxCoarse = 256;             // digits of the coarse level (one counter per lane)
 constexpr uint32_t kMaxTiles = 32768;            // tiles a call may span (LDS histogram, plan tables)
 constexpr uint32_t kHotWords = kMaxTiles / 32;   // words of the hot-tile bitmap
-#ifndef MLF_PART_THREADS
-#define MLF_PART_THREADS 1024
-#endif
-#ifndef MLF_CURSOR_STRIDE
-#define MLF_CURSOR_STRIDE 32
-#endif
-constexpr int kPartThreads = MLF_PART_THREADS;   // lanes of a partition workgroup
-#ifndef MLF_PART_ITEMS
-#define MLF_PART_ITEMS 8
-#endif
-constexpr int kPartItems = MLF_PART_ITEMS;       // records per lane in a partition step
+constexpr int kPartThreads = 1024;               // lanes of a partition workgroup
+constexpr int kPartItems = 8;                    // records per lane in a partition step
 constexpr uint32_t kPartTile = kPartThreads * kPartItems;      // records per step
+constexpr unsigned kCoarseWorkgroups = 512;      // persistent workgroups of the coarse level (2 per CU)
+constexpr int kCoarseLdsTopics = 8192;           // coarse level: totals privatised in LDS up to 32 KiB
 // Output cursors sit this many words apart: every partition step of a range
 // bumps the same cursors, and atomics on one cache line are served one by one.
-constexpr uint32_t kCursorStride = MLF_CURSOR_STRIDE;
-constexpr int kAccThreads = MLF_ACC_THREADS;     // lanes of an accumulate workgroup
-constexpr uint32_t kAccChunk = 1u << MLF_ACC_CHUNK_BITS;   // records per accumulate work item
-#ifndef MLF_SCAN_UNROLL
-#define MLF_SCAN_UNROLL 2
-#endif
-#ifndef MLF_SCAN_BLOCK
-#define MLF_SCAN_BLOCK 1024
-#endif
-#ifndef MLF_SCAN_WGS
-#define MLF_SCAN_WGS 512
-#endif
-constexpr int kScanBlock = MLF_SCAN_BLOCK;                    // lanes of a first-pass workgroup
-constexpr int kScanWorkgroups = MLF_SCAN_WGS;                 // first-pass workgroups of a call, about
-constexpr int kScanUnroll = MLF_SCAN_UNROLL;                  // triples per lane and step of the first pass
-constexpr int kPlanThreads = 1024;                            // lanes of the one plan workgroup
+constexpr uint32_t kCursorStride = 32;
+constexpr int kAccThreads = 1024;                // lanes of an accumulate workgroup
+constexpr uint32_t kAccChunk = 1u << 18;         // records per accumulate work item
+constexpr int kScanBlock = 1024;                 // lanes of a direct-path / sample workgroup
+constexpr int kScanWorkgroups = 512;             // direct-path workgroups of a call, about
+constexpr int kScanUnroll = 2;                   // triples per lane and step of the direct path
+constexpr int kPlanThreads = 1024;               // lanes of the one plan workgroup
+// The sample: blocks of kSampleBlock consecutive triples, every `period`-th
+// block of each buffer; period = n / (kSamplePerTile * tiles), i.e. about
+// kSamplePerTile sampled triples per tile, at most kSampleMaxPeriod and at
+// least 1 (then the "sample" is every triple and the plan is exact).
+constexpr long long kSampleBlock = 256;
+constexpr long long kSampleMaxPeriod = 64;
+constexpr long long kSamplePerTile = 256;
+constexpr unsigned kSampleWorkgroups = 128;
+// Room per tile: (h + kRoomSigmas * sqrt(h) + kRoomFloor) * (triples per sampled
+// triple), h = the tile's count in the sample.
+constexpr float kRoomSigmas = 5.0f;
+constexpr float kRoomFloor = 8.0f;
 // The binned path has a fixed cost (six launches, one accumulate workgroup per
 // non-empty tile); the direct path is cheaper below about this many triples
 // (measured crossovers: 0.25 M triples on a 31-tile matrix, 2 M on 3,052 tiles).
@@ -93,11 +85,15 @@ constexpr long long kMinBinnedTriplesPerTile = 600;
 struct SparseArgs {
     const int32_t *triples[MLF_MAX_K];
     long long n_triples[MLF_MAX_K];
+    uint32_t step_start[MLF_MAX_K + 1];  // coarse partition steps in the buffers before each one
+    uint32_t sample_start[MLF_MAX_K + 1];// sampled blocks in the buffers before each one
     int32_t *counts;
     int32_t *totals;
     int32_t *rejected;
     int V;
     int T;
+    int n_buffers;                       // buffers that hold triples
+    int sample_period;                   // every sample_period-th block of kSampleBlock triples is sampled
 };
 
 // A triple reduced to what the binned path needs: flat cell index and delta.
@@ -106,20 +102,26 @@ struct Record {
     int32_t delta;
 };
 
-// Records travel through the scratch in one of two formats.  LDA deltas are
-// almost always +-1, so when every delta of the call lies in
-// [-kSmallDeltaLimit, kSmallDeltaLimit) a record is ONE word: between the two
-// partition levels the coarse range is implied by where the record lies, which
-// leaves kCoarseShift bits of cell index and the rest for the delta; after the
-// fine level only the kTileBits cell bits inside the tile are needed.  Otherwise
-// (flag raised by the first pass) records are the full 8 bytes.
+// Records travel through the scratch as ONE word.  Between the two partition
+// levels the coarse range is implied by where the record lies, which leaves
+// kCoarseShift bits of cell index and the rest for the delta; after the fine
+// level only the kTileBits cell bits inside the tile are needed.  LDA deltas are
+// almost always +-1.  A delta outside [-kSmallDeltaLimit, kSmallDeltaLimit)
+// never becomes a record: the coarse level adds it to counts[] with a global
+// atomic instead, which costs what the direct path costs for that triple.  A
+// zero delta changes nothing and is dropped.
 constexpr int kCoarseShift = kTileBits + kFineBits;
 constexpr int32_t kSmallDeltaLimit = 1 << (31 - kCoarseShift);
 
-// The one-word forms of a record.
 __device__ __forceinline__ uint32_t pack_tmp(Record r)
 {
     return (r.cell & ((1u << kCoarseShift) - 1)) | (static_cast<uint32_t>(r.delta) << kCoarseShift);
+}
+
+__device__ __forceinline__ Record unpack_tmp(uint32_t v, uint32_t coarse)
+{
+    return Record{(coarse << kCoarseShift) | (v & ((1u << kCoarseShift) - 1)),
+                  static_cast<int32_t>(v) >> kCoarseShift};
 }
 
 __device__ __forceinline__ uint32_t pack_sorted(Record r)
@@ -127,76 +129,41 @@ __device__ __forceinline__ uint32_t pack_sorted(Record r)
     return (r.cell & (kTileCells - 1)) | (static_cast<uint32_t>(r.delta) << kTileBits);
 }
 
-template <bool WIDE>
-__device__ __forceinline__ void store_tmp(void *tmp, uint32_t i, Record r)
-{
-    if constexpr (WIDE) {
-        static_cast<Record *>(tmp)[i] = r;
-    } else {
-        static_cast<uint32_t *>(tmp)[i] = pack_tmp(r);
-    }
-}
-
-template <bool WIDE>
-__device__ __forceinline__ Record load_tmp(const void *tmp, uint32_t i, uint32_t coarse)
-{
-    if constexpr (WIDE) {
-        return static_cast<const Record *>(tmp)[i];
-    } else {
-        const uint32_t v = static_cast<const uint32_t *>(tmp)[i];
-        return Record{(coarse << kCoarseShift) | (v & ((1u << kCoarseShift) - 1)),
-                      static_cast<int32_t>(v) >> kCoarseShift};
-    }
-}
-
-template <bool WIDE>
-__device__ __forceinline__ void store_sorted(void *sorted, uint32_t i, Record r)
-{
-    if constexpr (WIDE) {
-        static_cast<Record *>(sorted)[i] = r;
-    } else {
-        static_cast<uint32_t *>(sorted)[i] = pack_sorted(r);
-    }
-}
-
-// Returns the cell index inside the tile and the delta.
-template <bool WIDE>
-__device__ __forceinline__ Record load_sorted(const void *sorted, uint32_t i)
-{
-    if constexpr (WIDE) {
-        const Record r = static_cast<const Record *>(sorted)[i];
-        return Record{r.cell & (kTileCells - 1), r.delta};
-    } else {
-        const uint32_t v = static_cast<const uint32_t *>(sorted)[i];
-        return Record{v & (kTileCells - 1), static_cast<int32_t>(v) >> kTileBits};
-    }
-}
-
-// Control block of the binned path, carved out of the caller's scratch.
+// Control block of the binned path, carved out of the caller's scratch.  All
+// the "start" tables describe ROOM (planned from the sample); how many records
+// actually arrived in a group is the smaller of its cursor and its room.
 struct BinPlan {
-    uint32_t *hist;               // [n_tiles]   records per tile            (zeroed)
-    uint32_t *coarse_cursor;      // [kMaxCoarse * kCursorStride] records placed so far per digit of the
-                                  //                             coarse level (zeroed)
-    uint32_t *fine_cursor;        // [n_tiles * kCursorStride]  records placed so far (zeroed)
-    uint32_t *tile_start;         // [n_tiles+1] exclusive scan of hist
-    uint32_t *coarse_part_start;  // [n_coarse+1] partition steps before each coarse range
+    uint32_t *hist;               // [n_tiles]   sampled triples per tile    (zeroed)
+    uint32_t *coarse_cursor;      // [kMaxCoarse * kCursorStride] records that asked for a place per
+                                  //                             digit of the coarse level (zeroed)
+    uint32_t *fine_cursor;        // [n_tiles * kCursorStride]  the same per tile, fine level (zeroed)
+    uint32_t *tile_start;         // [n_tiles+1] where each tile's room begins in `sorted`
+    uint32_t *coarse_part_start;  // [n_coarse+1] fine partition steps before each coarse range
     uint32_t *chunk_start;        // [n_tiles+1] accumulate work items of the tiles that are not hot,
                                   //             before each tile
     uint32_t *hot_chunk_start;    // [kMaxCoarse+1] accumulate work items before each hot tile; the hot
                                   //             tiles' items come first in the launch
     uint32_t *hot_tile;           // [kMaxCoarse] tile of each hot digit
-    uint32_t *tmp_start;          // [n_coarse+1] first record of each coarse range in tmp
+    uint32_t *tmp_start;          // [n_coarse+1] where each coarse range's room begins in `tmp`
     uint32_t *digit_start;        // [kMaxCoarse] first output index of each digit of the coarse level:
                                   //              in tmp for a coarse range, in sorted for a hot tile
+    uint32_t *digit_room;         // [kMaxCoarse] room of each digit of the coarse level
     uint32_t *hot_bits;           // [kHotWords] bit b set = tile b is hot
     uint32_t *hot_before;         // [kHotWords] hot tiles before the first tile of each word
-    uint32_t *wide_flag;          // [1] non-zero: some delta needs the 8-byte record (zeroed)
-    void *tmp;                    // [n] records grouped by coarse range
-    void *sorted;                 // [n] records grouped by tile
+    uint32_t *tmp;                // [n_slots] records grouped by coarse range
+    uint32_t *sorted;             // [n_slots] records grouped by tile
     uint32_t n_tiles;
     uint32_t n_coarse;
+    uint32_t n_slots;             // words in tmp and in sorted
+    float per_sampled;            // triples of the call per sampled triple (>= 1)
     unsigned long long n_cells;   // V * T
 };
+
+// Records of a group: what asked for a place, capped by the room.
+__device__ __forceinline__ uint32_t arrived(const uint32_t *cursor, uint32_t room)
+{
+    return min(*cursor, room);
+}
 
 __device__ __forceinline__ void add_relaxed(int32_t *p, int32_t v)
 {
@@ -285,34 +252,20 @@ __device__ __forceinline__ bool load_triple(const int32_t *tr, long long r, int 
            static_cast<unsigned>(topic) < static_cast<unsigned>(T);
 }
 
-// First pass over the triples; blockIdx.y = worker buffer, blockIdx.x = share
-// of that buffer.  BINNED = false: the direct path (counts[] updated here).
-// BINNED = true: only the per-tile histogram is built.  Both keep the totals in
-// LDS and count the rejected triples.
-// LDS: [T totals if LDS_TOTALS][n_tiles histogram if BINNED], dynamic up to
-// 64 KiB; BIG = a static array instead, for histograms of up to kMaxTiles tiles
-// with up to kBigTopics totals.
-constexpr int kBigTopics = 4096;
-
-template <bool BINNED, bool LDS_TOTALS, bool BIG = false>
-__global__ __launch_bounds__(kScanBlock) void scan_triples_kernel(const SparseArgs a,
-                                                                const BinPlan plan)
+// Direct path; blockIdx.y = worker buffer, blockIdx.x = share of that buffer.
+// Every valid triple is added to counts[] with a global atomic; the totals are
+// kept in LDS (dynamic, T entries) when LDS_TOTALS, and the rejected triples
+// are counted.
+template <bool LDS_TOTALS>
+__global__ __launch_bounds__(kScanBlock) void direct_kernel(const SparseArgs a)
 {
-    extern __shared__ int32_t dynamic_lds[];
-    __shared__ int32_t static_lds[BIG ? kMaxTiles + kBigTopics : 1];
-    int32_t *lds = BIG ? static_lds : dynamic_lds;
+    extern __shared__ int32_t lds_totals[];
     const int T = a.T;
     const bool want_totals = a.totals != nullptr;
-    int32_t *lds_totals = lds;
-    uint32_t *lds_hist = reinterpret_cast<uint32_t *>(lds + (LDS_TOTALS ? T : 0));
     if constexpr (LDS_TOTALS) {
         for (int t = threadIdx.x; t < T; t += kScanBlock) lds_totals[t] = 0;
+        __syncthreads();
     }
-    if constexpr (BINNED) {
-        for (uint32_t b = threadIdx.x; b < plan.n_tiles; b += kScanBlock) lds_hist[b] = 0;
-    }
-    if constexpr (LDS_TOTALS || BINNED) __syncthreads();
-
     const int k = blockIdx.y;
     const int32_t *tr = a.triples[k];
     const long long m = a.n_triples[k];
@@ -324,7 +277,6 @@ __global__ __launch_bounds__(kScanBlock) void scan_triples_kernel(const SparseAr
     const long long begin = min(static_cast<long long>(blockIdx.x) * share, m);
     const long long end = min(begin + share, m);
     int n_bad = 0;
-    bool wide = false;
     // kScanUnroll triples per lane and step, all loaded before the first is used.
     for (long long r0 = begin + threadIdx.x; r0 < end; r0 += kStep) {
         int word[kScanUnroll], topic[kScanUnroll], delta[kScanUnroll];
@@ -343,13 +295,7 @@ __global__ __launch_bounds__(kScanBlock) void scan_triples_kernel(const SparseAr
                 ++n_bad;
                 continue;
             }
-            const long long cell = static_cast<long long>(word[u]) * T + topic[u];
-            if constexpr (BINNED) {
-                wide = wide || delta[u] < -kSmallDeltaLimit || delta[u] >= kSmallDeltaLimit;
-                wave_count(lds_hist, static_cast<uint32_t>(cell) >> kTileBits);
-            } else {
-                add_relaxed(a.counts + cell, delta[u]);
-            }
+            add_relaxed(a.counts + (static_cast<long long>(word[u]) * T + topic[u]), delta[u]);
             if (want_totals) {
                 if constexpr (LDS_TOTALS) {
                     lds_add(&lds_totals[topic[u]], delta[u]);
@@ -359,9 +305,8 @@ __global__ __launch_bounds__(kScanBlock) void scan_triples_kernel(const SparseAr
             }
         }
     }
-
-    if constexpr (LDS_TOTALS || BINNED) __syncthreads();
     if constexpr (LDS_TOTALS) {
+        __syncthreads();
         if (want_totals) {
             for (int t = threadIdx.x; t < T; t += kScanBlock) {
                 const int32_t v = lds_totals[t];
@@ -369,20 +314,76 @@ __global__ __launch_bounds__(kScanBlock) void scan_triples_kernel(const SparseAr
             }
         }
     }
-    if constexpr (BINNED) {
-        for (uint32_t b = threadIdx.x; b < plan.n_tiles; b += kScanBlock) {
-            const uint32_t v = lds_hist[b];
-            if (v != 0) fetch_add_relaxed(plan.hist + b, v);
-        }
-        // One lane per wavefront raises the flag if any lane met a large delta.
-        if (__ballot(wide) != 0 && (threadIdx.x & 63) == 0) {
-            __hip_atomic_fetch_or(plan.wide_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-    }
     if (a.rejected != nullptr) {
         // Wavefront sum of the per-lane reject counts, one atomic per wavefront.
         for (int off = 32; off > 0; off >>= 1) n_bad += __shfl_down(n_bad, off, 64);
         if ((threadIdx.x & 63) == 0 && n_bad != 0) add_relaxed(a.rejected, n_bad);
+    }
+}
+
+// The sample of the binned path: per-tile counts of the valid, record-sized
+// triples in every sample_period-th block of kSampleBlock triples of every
+// buffer.  The sampled blocks of all buffers form one list; a quarter of a
+// workgroup takes a block, and every lane has the loads of kSampleUnroll blocks
+// in flight.  The histogram is built in LDS (dynamic, n_tiles words; BIG = a
+// static array for more than 16,384 tiles) and merged into plan.hist with one
+// atomic per non-empty bin.
+constexpr int kSampleUnroll = 4;
+
+template <bool BIG>
+__global__ __launch_bounds__(kScanBlock) void sample_kernel(const SparseArgs a, const BinPlan plan)
+{
+    extern __shared__ int32_t dynamic_lds[];
+    __shared__ int32_t static_lds[BIG ? kMaxTiles : 1];
+    uint32_t *lds_hist = reinterpret_cast<uint32_t *>(BIG ? static_lds : dynamic_lds);
+    // The per-buffer tables are looked up per lane: from LDS, not from the
+    // kernel-argument segment (a chain of dependent global loads otherwise).
+    __shared__ uint32_t s_start[MLF_MAX_K + 1];
+    __shared__ long long s_count[MLF_MAX_K];
+    __shared__ const int32_t *s_triples[MLF_MAX_K];
+    for (uint32_t b = threadIdx.x; b < plan.n_tiles; b += kScanBlock) lds_hist[b] = 0;
+    if (threadIdx.x <= MLF_MAX_K) s_start[threadIdx.x] = a.sample_start[threadIdx.x];
+    if (threadIdx.x < MLF_MAX_K) {
+        s_count[threadIdx.x] = a.n_triples[threadIdx.x];
+        s_triples[threadIdx.x] = a.triples[threadIdx.x];
+    }
+    __syncthreads();
+    constexpr uint32_t kBlocksAtOnce = kScanBlock / kSampleBlock;     // sampled blocks per workgroup and load
+    const uint32_t within = threadIdx.x % kSampleBlock;
+    const uint32_t n_sampled = s_start[a.n_buffers];
+    const uint32_t stride = gridDim.x * kBlocksAtOnce;
+    for (uint32_t q0 = blockIdx.x * kBlocksAtOnce + threadIdx.x / kSampleBlock; q0 < n_sampled;
+         q0 += stride * kSampleUnroll) {
+        int word[kSampleUnroll], topic[kSampleUnroll], delta[kSampleUnroll];
+        bool ok[kSampleUnroll];
+#pragma unroll
+        for (int u = 0; u < kSampleUnroll; ++u) {
+            const uint32_t q = q0 + u * stride;                        // sampled block in the list
+            // its buffer: the last one that starts at or before q
+            int lo = 0, hi = a.n_buffers;
+            while (hi - lo > 1) {
+                const int mid = (lo + hi) / 2;
+                if (s_start[mid] <= q) lo = mid; else hi = mid;
+            }
+            const long long r = static_cast<long long>(q - s_start[lo]) * a.sample_period * kSampleBlock + within;
+            const long long m = s_count[lo];                           // >= 1
+            const bool there = q < n_sampled && r < m;
+            // (no branch around the load: a lane with nothing to sample reloads the last triple)
+            ok[u] = load_triple(s_triples[lo], there ? r : m - 1, a.V, a.T, word[u], topic[u], delta[u]) && there;
+        }
+#pragma unroll
+        for (int u = 0; u < kSampleUnroll; ++u) {
+            if (ok[u] && delta[u] != 0 && delta[u] >= -kSmallDeltaLimit && delta[u] < kSmallDeltaLimit) {
+                const uint32_t cell = static_cast<uint32_t>(word[u]) * static_cast<uint32_t>(a.T) +
+                                      static_cast<uint32_t>(topic[u]);
+                wave_count(lds_hist, cell >> kTileBits);
+            }
+        }
+    }
+    __syncthreads();
+    for (uint32_t b = threadIdx.x; b < plan.n_tiles; b += kScanBlock) {
+        const uint32_t v = lds_hist[b];
+        if (v != 0) fetch_add_relaxed(plan.hist + b, v);
     }
 }
 
@@ -435,64 +436,84 @@ __device__ __forceinline__ void block_scan(const uint32_t (&v)[N], uint32_t (&ex
     __syncthreads();
 }
 
-// One workgroup: turns the tile histogram into the offsets every later step uses.
+// One workgroup: turns the sampled tile histogram into the room every later
+// step works in.
+//
+// Room of a tile: (h + kRoomSigmas * sqrt(h) + kRoomFloor) * per_sampled records,
+// h = its count in the sample; the running total is cut off at n_slots, the size
+// of the arrays, so that whatever the sample says no index leaves them.
 //
 // Heavy tiles skip the fine level.  The coarse level has kMaxCoarse digits and
 // needs n_coarse of them for the coarse ranges; each spare digit is given to one
 // of the heaviest tiles ("hot"), whose records the coarse level then writes
 // straight to their final place in `sorted`.  Under a Zipf law a few hundred
 // tiles hold most of the records, so most records are moved once instead of
-// twice.  The hot tiles are those with at least `threshold` records, the
-// smallest power-of-two fraction of the total that leaves no more hot tiles
+// twice.  The hot tiles are those with at least `threshold` sampled triples,
+// the smallest power-of-two fraction of the sample that leaves no more hot tiles
 // than spare digits.  They are published as a bitmap plus, per bitmap word, the
 // number of hot tiles before it, so that a lane finds the digit of a tile with
 // one LDS read and a population count.
 //
 // Lane i looks after the tiles i, i + kPlanThreads, ... (one per round); the
-// record counts are kept in LDS, and every table over the tiles is a running
-// block scan over the rounds.  (The rounds are loops, not unrolled: the kernel
-// runs once per call, and straight-line code would be fetched from memory once.)
-#ifndef MLF_HOT_SHIFTS
-#define MLF_HOT_SHIFTS 24
-#endif
-constexpr int kHotShifts = MLF_HOT_SHIFTS;     // a hot tile holds at least total >> (kHotShifts - 1) records
+// rooms are kept in LDS, and every table over the tiles is a running block scan
+// over the rounds.  (The rounds are loops, not unrolled: the kernel runs once
+// per call, and straight-line code would be fetched from memory once.)
+constexpr int kHotShifts = 24;      // a hot tile holds at least total >> (kHotShifts - 1) sampled triples
 
 __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const BinPlan plan)
 {
     static_assert(kMaxCoarse <= kPlanThreads, "the tables over coarse digits take one round");
     __shared__ uint32_t wave_sums[3][kPlanWaves];
     __shared__ uint32_t tiles_at_least[kHotShifts];
-    __shared__ uint32_t hot_in_range[kMaxCoarse];     // hot records per coarse range
+    __shared__ uint32_t hot_in_range[kMaxCoarse];     // room of the hot tiles of each coarse range
     __shared__ uint32_t s_threshold;
-    __shared__ uint32_t h[kMaxTiles];                 // records per tile
+    __shared__ uint32_t room[kMaxTiles];              // room per tile
     const uint32_t n_tiles = plan.n_tiles;
     const uint32_t n_coarse = plan.n_coarse;
+    const uint32_t n_slots = plan.n_slots;
     const uint32_t lane = threadIdx.x & 63;
 
     if (threadIdx.x < kHotShifts) tiles_at_least[threadIdx.x] = 0;
     if (threadIdx.x < kMaxCoarse) hot_in_range[threadIdx.x] = 0;
 
-    // tile_start: exclusive scan of the histogram.
-    uint32_t total = 0;
+    // tile_start: exclusive scan of the rooms, cut off at n_slots; and the
+    // size of the sample.
+    uint32_t placed = 0, sample = 0;
 #pragma unroll 1
     for (uint32_t base = 0; base < n_tiles; base += kPlanThreads) {
         const uint32_t b = base + threadIdx.x;
-        const uint32_t v[1] = {b < n_tiles ? plan.hist[b] : 0u};
-        h[b] = v[0];
-        uint32_t e[1], t[1];
-        block_scan<1>(v, e, t, wave_sums);
-        if (b < n_tiles) plan.tile_start[b] = total + e[0];
-        total += t[0];
+        const uint32_t h = b < n_tiles ? plan.hist[b] : 0u;
+        const float hf = static_cast<float>(h);
+        const float want = (hf + kRoomSigmas * sqrtf(hf) + kRoomFloor) * plan.per_sampled + 1.0f;
+        // (want stays far below 2^32: h * per_sampled is about the tile's share of < 2^31 triples)
+        const uint32_t v[2] = {b < n_tiles ? static_cast<uint32_t>(fminf(want, 4.0e9f)) : 0u, h};
+        uint32_t e[2], t[2];
+        block_scan<2>(v, e, t, wave_sums);
+        // Saturating: once the running total has reached n_slots every later room is 0.
+        const unsigned long long lo = static_cast<unsigned long long>(placed) + e[0];
+        const unsigned long long hi = lo + v[0];
+        const uint32_t start = lo < n_slots ? static_cast<uint32_t>(lo) : n_slots;
+        const uint32_t stop = hi < n_slots ? static_cast<uint32_t>(hi) : n_slots;
+        if (b < n_tiles) {
+            plan.tile_start[b] = start;
+            room[b] = stop - start;
+        } else if (b < kMaxTiles) {
+            room[b] = 0;
+        }
+        const unsigned long long all = static_cast<unsigned long long>(placed) + t[0];
+        placed = all < n_slots ? static_cast<uint32_t>(all) : n_slots;
+        sample += t[1];
     }
-    if (threadIdx.x == 0) plan.tile_start[n_tiles] = total;
+    if (threadIdx.x == 0) plan.tile_start[n_tiles] = placed;
 
-    // Threshold of the hot tiles.
+    // Threshold of the hot tiles (on the sampled counts).
 #pragma unroll 1
     for (uint32_t base = 0; base < n_tiles; base += kPlanThreads) {
-        const uint32_t mine = h[base + threadIdx.x];
+        const uint32_t b = base + threadIdx.x;
+        const uint32_t mine = b < n_tiles ? plan.hist[b] : 0u;
 #pragma unroll 1
         for (int j = 0; j < kHotShifts; ++j) {
-            const unsigned long long heavy = __ballot(mine != 0 && mine >= (total >> j));
+            const unsigned long long heavy = __ballot(mine != 0 && mine >= (sample >> j));
             if (lane == 0 && heavy != 0) {
                 lds_fetch_add(&tiles_at_least[j], static_cast<uint32_t>(__popcll(heavy)));
             }
@@ -503,7 +524,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const BinPlan plan)
         const uint32_t spare = kMaxCoarse - n_coarse;
         uint32_t threshold = 0xffffffffu;                    // no hot tile
         for (int j = 0; j < kHotShifts; ++j) {
-            if (tiles_at_least[j] <= spare && (total >> j) >= 1) threshold = total >> j;
+            if (tiles_at_least[j] <= spare && (sample >> j) >= 1) threshold = sample >> j;
         }
         s_threshold = threshold;
     }
@@ -511,14 +532,16 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const BinPlan plan)
     const uint32_t threshold = s_threshold;
 
     // Hot tiles: bitmap (the words that cover the call's tiles), digit of each
-    // (its rank among the hot tiles), hot records per coarse range; and the
-    // accumulate work items (kAccChunk records each) of the tiles that are not hot.
+    // (its rank among the hot tiles), hot room per coarse range; and the
+    // accumulate work items (kAccChunk records of room each) of the tiles that
+    // are not hot.
     uint32_t n_hot = 0, n_items = 0;
 #pragma unroll 1
     for (uint32_t base = 0; base < n_tiles; base += kPlanThreads) {
         const uint32_t b = base + threadIdx.x;
-        const uint32_t mine = h[b];
-        const bool hot = mine != 0 && mine >= threshold;
+        const uint32_t sampled = b < n_tiles ? plan.hist[b] : 0u;
+        const uint32_t mine = room[b];
+        const bool hot = sampled != 0 && sampled >= threshold;
         const unsigned long long mask = __ballot(hot);
         if (lane == 0) {
             plan.hot_bits[b >> 5] = static_cast<uint32_t>(mask);
@@ -532,6 +555,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const BinPlan plan)
         if (hot) {
             plan.hot_tile[slot] = b;
             plan.digit_start[n_coarse + slot] = plan.tile_start[b];      // this lane wrote it
+            plan.digit_room[n_coarse + slot] = mine;
             lds_fetch_add(&hot_in_range[b >> kFineBits], mine);
         }
         if (b < n_tiles) plan.chunk_start[b] = n_items + e[1];
@@ -545,10 +569,10 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const BinPlan plan)
     __syncthreads();
     __threadfence_block();
 
-    // Per coarse range: the records that still go through the fine level and
-    // their partition steps (kPartTile records each); per hot digit: the
-    // accumulate work items of its tile, which come first in that launch so
-    // that the long ones start early.
+    // Per coarse range: the room of its tiles that still go through the fine
+    // level, and the fine partition steps (kPartTile records each) that room
+    // takes; per hot digit: the accumulate work items of its tile, which come
+    // first in that launch so that the long ones start early.
     {
         const uint32_t c = threadIdx.x;
         uint32_t cold = 0;
@@ -558,18 +582,23 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const BinPlan plan)
             cold = plan.tile_start[hi] - plan.tile_start[lo] - hot_in_range[c];
         }
         uint32_t hot_items = 0;
-        if (c < n_hot) hot_items = (h[plan.hot_tile[c]] + kAccChunk - 1) / kAccChunk;
+        if (c < n_hot) hot_items = (room[plan.hot_tile[c]] + kAccChunk - 1) / kAccChunk;
         const uint32_t v[3] = {cold, (cold + kPartTile - 1) / kPartTile, hot_items};
         uint32_t e[3], t[3];
         block_scan<3>(v, e, t, wave_sums);
         if (c < n_coarse) {
-            plan.tmp_start[c] = e[0];
+            plan.tmp_start[c] = e[0];          // the cold rooms add up to at most n_slots
             plan.digit_start[c] = e[0];
+            plan.digit_room[c] = cold;
             plan.coarse_part_start[c] = e[1];
         }
         if (c == n_coarse) {
             plan.tmp_start[c] = t[0];
             plan.coarse_part_start[c] = t[1];
+        }
+        if (c >= n_coarse + n_hot && c < kMaxCoarse) {
+            plan.digit_start[c] = 0;           // digits nobody uses
+            plan.digit_room[c] = 0;
         }
         if (c <= kMaxCoarse) plan.hot_chunk_start[c] = c < kMaxCoarse ? e[2] : t[2];
     }
@@ -598,37 +627,35 @@ __device__ __forceinline__ uint32_t owner_of(const uint32_t *start, uint32_t n, 
 // One partition step of a workgroup: up to kPartTile records held in registers
 // are grouped by digit (< kMaxCoarse) in LDS and written out so that the records
 // of one digit form one contiguous run at the place reserved for them.
-//   rec[i], live[i]  the lane's records and whether each exists
-//   digit_of(cell)   digit of a record
-//   reserve(d, n)    output index where this step's n records of digit d go
-// Eight-byte records (WIDE) are staged as they are and placed when they are
-// written out:
-//   emit(d, i, r)    writes record r of digit d at output index i
-// One-word records are packed and given their output index when they are
-// staged, so that writing them out is a copy:
-//   pack(d, r)       the word to store for record r of digit d; bit 31 of the
-//                    result's `where` selects the output array
-//   copy(where, w)   stores word w at output index (where & 0x7fffffff)
+//   rec[i], live[i]     the lane's records and whether each exists
+//   digit_of(cell)      digit of a record
+//   reserve(d, n, room) output index where this step's n records of digit d go;
+//                       sets `room` to how many of them still fit there
+//   pack(d, r)          the word to store for record r of digit d; bit 31 of the
+//                       result's `where` selects the output array
+//   copy(where, w)      stores word w at output index (where & 0x7fffffff)
+//   spill(r)            takes a record that found its group full
+// Records are packed and given their output index when they are staged, so
+// that writing them out is a copy.  Must be entered by the whole workgroup, with
+// s.count[] zero; leaves s.count[] zero again.
 struct Staged {
     uint32_t word;
     uint32_t where;
 };
+constexpr uint32_t kNowhere = 0xffffffffu;      // a staged slot whose record was spilled
 
 struct PartitionLds {
-    union {
-        Record wide[kPartTile];
-        Staged narrow[kPartTile];
-    } stage;
+    Staged stage[kPartTile];
     uint32_t count[kMaxCoarse];
-    uint32_t offset[kMaxCoarse];
-    uint32_t dest[kMaxCoarse];
+    uint4 place[kMaxCoarse];     // per digit: x = first staging slot, y = first output index,
+                                 // z = records of this step that still fit there (one 128-bit read)
     uint32_t total;
 };
 
-template <bool WIDE, typename DigitOf, typename Reserve, typename Emit, typename Pack, typename Copy>
+template <typename DigitOf, typename Reserve, typename Pack, typename Copy, typename Spill>
 __device__ __forceinline__ void partition_step(PartitionLds &s, const Record (&rec)[kPartItems],
                                                const bool (&live)[kPartItems], DigitOf digit_of,
-                                               Reserve reserve, Emit emit, Pack pack, Copy copy)
+                                               Reserve reserve, Pack pack, Copy copy, Spill spill)
 {
     static_assert(kMaxCoarse == 256 && kPartThreads >= 256, "one wavefront scans 4 digits per lane");
     uint32_t dig[kPartItems], rank[kPartItems];
@@ -657,161 +684,162 @@ __device__ __forceinline__ void partition_step(PartitionLds &s, const Record (&r
         uint32_t run = incl - sum;
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
-            s.offset[4 * lane + k] = run;
+            s.place[4 * lane + k].x = run;
             run += c[k];
         }
         if (lane == 63) s.total = incl;
     }
-    if (threadIdx.x < kMaxCoarse) {
-        const uint32_t mine = s.count[threadIdx.x];
-        if (mine != 0) s.dest[threadIdx.x] = reserve(threadIdx.x, mine);
+    if (threadIdx.x >= 64 && threadIdx.x < 64 + kMaxCoarse) {
+        const uint32_t d = threadIdx.x - 64;
+        const uint32_t mine = s.count[d];
+        if (mine != 0) {
+            uint32_t fits = 0;
+            s.place[d].y = reserve(d, mine, fits);
+            s.place[d].z = fits;
+        }
     }
     __syncthreads();
-    if constexpr (WIDE) {
-#pragma unroll
-        for (int i = 0; i < kPartItems; ++i) {
-            if (live[i]) s.stage.wide[s.offset[dig[i]] + rank[i]] = rec[i];
-        }
-        __syncthreads();
-        const uint32_t total = s.total;
-        for (uint32_t i = threadIdx.x; i < total; i += kPartThreads) {
-            const Record r = s.stage.wide[i];
-            const uint32_t d = digit_of(r.cell);
-            emit(d, s.dest[d] + (i - s.offset[d]), r);
-        }
-    } else {
-#pragma unroll
-        for (int i = 0; i < kPartItems; ++i) {
-            if (live[i]) {
-                Staged e = pack(dig[i], rec[i]);
-                e.where |= s.dest[dig[i]] + rank[i];
-                s.stage.narrow[s.offset[dig[i]] + rank[i]] = e;
-            }
-        }
-        __syncthreads();
-        const uint32_t total = s.total;
-        for (uint32_t i = threadIdx.x; i < total; i += kPartThreads) {
-            const Staged e = s.stage.narrow[i];
-            copy(e.where, e.word);
-        }
-    }
-}
-
-// Coarse partition: blockIdx.y = worker buffer, blockIdx.x = step within it.
-// Valid triples become records: those of hot tiles go to their final place in
-// plan.sorted, the others to plan.tmp, grouped by coarse range.
-struct HotLds {
-    uint2 word[kHotWords];      // x = bitmap word, y = hot tiles before it: one 64-bit read per lookup
-};
-
-template <bool WIDE>
-__device__ __forceinline__ void coarse_partition_body(PartitionLds &s, HotLds &hot,
-                                                      const SparseArgs &a, const BinPlan &plan)
-{
-    const int32_t *tr = a.triples[blockIdx.y];
-    const long long m = a.n_triples[blockIdx.y];
-    const long long base = static_cast<long long>(blockIdx.x) * kPartTile;
-    if (base >= m) return;                               // uniform for the workgroup
-    Record rec[kPartItems];
-    bool live[kPartItems];
+    if (threadIdx.x < kMaxCoarse) s.count[threadIdx.x] = 0;     // for the next step
 #pragma unroll
     for (int i = 0; i < kPartItems; ++i) {
-        const long long r = base + i * kPartThreads + threadIdx.x;
-        int word = 0, topic = 0, delta = 0;
-        live[i] = r < m && load_triple(tr, r, a.V, a.T, word, topic, delta);
-        rec[i].cell = static_cast<uint32_t>(static_cast<long long>(word) * a.T + topic);
-        rec[i].delta = delta;
-    }
-    // The hot-tile bitmap and the digit counters, while the triples are in flight.
-    static_assert(kHotWords <= kPartThreads && kMaxCoarse <= kPartThreads, "one word per lane");
-    if (threadIdx.x < (plan.n_tiles + 31) / 32) {       // the words that cover the call's tiles
-        hot.word[threadIdx.x] = make_uint2(plan.hot_bits[threadIdx.x], plan.hot_before[threadIdx.x]);
-    }
-    if (threadIdx.x < kMaxCoarse) s.count[threadIdx.x] = 0;
-    __syncthreads();
-    const uint32_t n_coarse = plan.n_coarse;
-    const HotLds *h = &hot;
-    uint32_t *tmp_words = static_cast<uint32_t *>(plan.tmp);
-    uint32_t *sorted_words = static_cast<uint32_t *>(plan.sorted);
-    partition_step<WIDE>(
-        s, rec, live,
-        [=](uint32_t cell) {
-            const uint32_t tile = cell >> kTileBits;
-            const uint2 entry = h->word[tile >> 5];
-            const uint32_t bit = tile & 31;
-            const uint32_t hot_digit =
-                n_coarse + entry.y + static_cast<uint32_t>(__popc(entry.x & ((1u << bit) - 1u)));
-            return ((entry.x >> bit) & 1u) != 0 ? hot_digit : tile >> kFineBits;
-        },
-        [=](uint32_t d, uint32_t n) {
-            return plan.digit_start[d] + fetch_add_relaxed(plan.coarse_cursor + d * kCursorStride, n);
-        },
-        [=](uint32_t d, uint32_t i, Record r) {
-            if (d < n_coarse) {
-                store_tmp<WIDE>(plan.tmp, i, r);
-            } else {
-                store_sorted<WIDE>(plan.sorted, i, r);
+        if (live[i]) {
+            const uint32_t d = dig[i];
+            const uint4 place = s.place[d];
+            Staged e = pack(d, rec[i]);
+            e.where |= place.y + rank[i];
+            if (rank[i] >= place.z) {
+                e.where = kNowhere;
+                spill(rec[i]);
             }
-        },
-        [=](uint32_t d, Record r) {
-            return d < n_coarse ? Staged{pack_tmp(r), 0u} : Staged{pack_sorted(r), 0x80000000u};
-        },
-        [=](uint32_t where, uint32_t word) {
-            uint32_t *out = (where >> 31) != 0 ? sorted_words : tmp_words;
-            out[where & 0x7fffffffu] = word;
-        });
+            s.stage[place.x + rank[i]] = e;
+        }
+    }
+    __syncthreads();
+    const uint32_t total = s.total;
+    for (uint32_t i = threadIdx.x; i < total; i += kPartThreads) {
+        const Staged e = s.stage[i];
+        if (e.where != kNowhere) copy(e.where, e.word);
+    }
 }
 
-// The record format of the call, the same for every lane (scalar register).
-__device__ __forceinline__ bool wide_records(const BinPlan &plan)
-{
-    return __builtin_amdgcn_readfirstlane(static_cast<int>(*plan.wide_flag)) != 0;
-}
-
+// Coarse partition, the one pass over the triples.  A persistent grid: the
+// workgroups take the steps (kPartTile triples of one buffer each) in turn and
+// keep the per-topic totals in LDS over all their steps.  Valid triples become
+// records: those of hot tiles go to their final place in plan.sorted, the others
+// to plan.tmp, grouped by coarse range.  A record whose group is full, and a
+// triple whose delta is too large for a record, is added to counts[] at once.
+// Dynamic LDS: [hot-tile table: 2 words per 32 tiles][T totals if LDS_TOTALS].
+template <bool LDS_TOTALS>
 __global__ __launch_bounds__(kPartThreads) void coarse_partition_kernel(const SparseArgs a,
                                                                     const BinPlan plan)
 {
+    extern __shared__ uint32_t coarse_lds[];
     __shared__ PartitionLds s;
-    __shared__ HotLds hot;
-    if (wide_records(plan)) {
-        coarse_partition_body<true>(s, hot, a, plan);
-    } else {
-        coarse_partition_body<false>(s, hot, a, plan);
-    }
-}
-
-// Fine partition: workgroup g takes one step of one coarse range of plan.tmp
-// and writes its records to plan.sorted, grouped by tile.
-template <bool WIDE>
-__device__ __forceinline__ void fine_partition_body(PartitionLds &s, const BinPlan &plan, uint32_t g,
-                                                    uint32_t c)
-{
-    const uint32_t first_tile = c << kFineBits;
-    const uint32_t begin = plan.tmp_start[c] + (g - plan.coarse_part_start[c]) * kPartTile;
-    const uint32_t end = min(begin + kPartTile, plan.tmp_start[c + 1]);
-    Record rec[kPartItems];
-    bool live[kPartItems];
-#pragma unroll
-    for (int i = 0; i < kPartItems; ++i) {
-        const uint32_t r = begin + i * kPartThreads + threadIdx.x;
-        live[i] = r < end;
-        rec[i] = live[i] ? load_tmp<WIDE>(plan.tmp, r, c) : Record{0u, 0};
+    const uint32_t hot_words = (plan.n_tiles + 31) / 32;
+    // x = bitmap word, y = hot tiles before it: one 64-bit read per lookup
+    uint2 *hot = reinterpret_cast<uint2 *>(coarse_lds);
+    int32_t *lds_totals = reinterpret_cast<int32_t *>(coarse_lds + 2 * hot_words);
+    const int T = a.T;
+    const bool want_totals = a.totals != nullptr;
+    static_assert(kHotWords <= kPartThreads && kMaxCoarse <= kPartThreads, "one word per lane");
+    if (threadIdx.x < hot_words) {
+        hot[threadIdx.x] = make_uint2(plan.hot_bits[threadIdx.x], plan.hot_before[threadIdx.x]);
     }
     if (threadIdx.x < kMaxCoarse) s.count[threadIdx.x] = 0;
+    if constexpr (LDS_TOTALS) {
+        for (int t = threadIdx.x; t < T; t += kPartThreads) lds_totals[t] = 0;
+    }
     __syncthreads();
-    uint32_t *sorted_words = static_cast<uint32_t *>(plan.sorted);
-    partition_step<WIDE>(
-        s, rec, live, [](uint32_t cell) { return (cell >> kTileBits) & (kFinePerCoarse - 1); },
-        [=](uint32_t f, uint32_t n) {
-            const uint32_t tile = first_tile + f;
-            return plan.tile_start[tile] + fetch_add_relaxed(plan.fine_cursor + tile * kCursorStride, n);
-        },
-        [=](uint32_t, uint32_t i, Record r) { store_sorted<WIDE>(plan.sorted, i, r); },
-        [](uint32_t, Record r) { return Staged{pack_sorted(r), 0u}; },
-        [=](uint32_t where, uint32_t word) { sorted_words[where] = word; });
+
+    const uint32_t n_coarse = plan.n_coarse;
+    uint32_t *tmp = plan.tmp;
+    uint32_t *sorted = plan.sorted;
+    int32_t *counts = a.counts;
+    const uint32_t n_steps = a.step_start[a.n_buffers];
+    int n_bad = 0;
+    int k = 0;                                              // buffer of the current step (uniform)
+#pragma unroll 1
+    for (uint32_t step = blockIdx.x; step < n_steps; step += gridDim.x) {
+        while (step >= a.step_start[k + 1]) ++k;            // steps only grow; k < n_buffers
+        const int32_t *tr = a.triples[k];
+        const long long m = a.n_triples[k];
+        const long long base = static_cast<long long>(step - a.step_start[k]) * kPartTile;
+        // All of the lane's triples are loaded before the first is used.
+        int word[kPartItems], topic[kPartItems], delta[kPartItems];
+        bool there[kPartItems], valid[kPartItems];
+#pragma unroll
+        for (int i = 0; i < kPartItems; ++i) {
+            const long long r = base + i * kPartThreads + threadIdx.x;
+            there[i] = r < m;
+            // (a lane past the end reloads the buffer's last triple: no branch
+            // around the load, so the loads of a lane issue back to back)
+            valid[i] = load_triple(tr, there[i] ? r : m - 1, a.V, T, word[i], topic[i], delta[i]) && there[i];
+        }
+        Record rec[kPartItems];
+        bool live[kPartItems];
+#pragma unroll
+        for (int i = 0; i < kPartItems; ++i) {
+            if (there[i] && !valid[i]) ++n_bad;
+            rec[i].cell = static_cast<uint32_t>(word[i]) * static_cast<uint32_t>(T) + static_cast<uint32_t>(topic[i]);
+            rec[i].delta = delta[i];
+            const bool small = delta[i] >= -kSmallDeltaLimit && delta[i] < kSmallDeltaLimit;
+            live[i] = valid[i] && small && delta[i] != 0;
+            if (valid[i] && !small) add_relaxed(counts + rec[i].cell, delta[i]);
+            if (valid[i] && want_totals && delta[i] != 0) {
+                if constexpr (LDS_TOTALS) {
+                    lds_add(&lds_totals[topic[i]], delta[i]);
+                } else {
+                    add_relaxed(a.totals + topic[i], delta[i]);
+                }
+            }
+        }
+        partition_step(
+            s, rec, live,
+            [=](uint32_t cell) {
+                const uint32_t tile = cell >> kTileBits;
+                const uint2 entry = hot[tile >> 5];
+                const uint32_t bit = tile & 31;
+                const uint32_t hot_digit =
+                    n_coarse + entry.y + static_cast<uint32_t>(__popc(entry.x & ((1u << bit) - 1u)));
+                return ((entry.x >> bit) & 1u) != 0 ? hot_digit : tile >> kFineBits;
+            },
+            [=](uint32_t d, uint32_t n, uint32_t &fits) {
+                const uint32_t before = fetch_add_relaxed(plan.coarse_cursor + d * kCursorStride, n);
+                const uint32_t room = plan.digit_room[d];
+                fits = before < room ? room - before : 0u;
+                return plan.digit_start[d] + before;
+            },
+            [=](uint32_t d, Record r) {
+                return d < n_coarse ? Staged{pack_tmp(r), 0u} : Staged{pack_sorted(r), 0x80000000u};
+            },
+            [=](uint32_t where, uint32_t word) {
+                uint32_t *out = (where >> 31) != 0 ? sorted : tmp;
+                out[where & 0x7fffffffu] = word;
+            },
+            [=](Record r) { add_relaxed(counts + r.cell, r.delta); });
+        __syncthreads();                                    // the stage is reused by the next step
+    }
+
+    if constexpr (LDS_TOTALS) {
+        __syncthreads();
+        if (want_totals) {
+            for (int t = threadIdx.x; t < T; t += kPartThreads) {
+                const int32_t v = lds_totals[t];
+                if (v != 0) add_relaxed(a.totals + t, v);
+            }
+        }
+    }
+    if (a.rejected != nullptr) {
+        // Wavefront sum of the per-lane reject counts, one atomic per wavefront.
+        for (int off = 32; off > 0; off >>= 1) n_bad += __shfl_down(n_bad, off, 64);
+        if ((threadIdx.x & 63) == 0 && n_bad != 0) add_relaxed(a.rejected, n_bad);
+    }
 }
 
-__global__ __launch_bounds__(kPartThreads) void fine_partition_kernel(const BinPlan plan)
+// Fine partition: workgroup g takes one step of the room of one coarse range of
+// plan.tmp and writes the records that arrived there to plan.sorted, grouped by
+// tile (or adds them to counts[] where a tile's room is full).
+__global__ __launch_bounds__(kPartThreads) void fine_partition_kernel(int32_t *counts, const BinPlan plan)
 {
     __shared__ PartitionLds s;
     __shared__ uint32_t s_coarse;
@@ -821,45 +849,63 @@ __global__ __launch_bounds__(kPartThreads) void fine_partition_kernel(const BinP
         const uint32_t c = owner_of(plan.coarse_part_start, plan.n_coarse, g);
         if (threadIdx.x == 0) s_coarse = c;
     }
+    if (threadIdx.x < kMaxCoarse) s.count[threadIdx.x] = 0;
     __syncthreads();
     const uint32_t c = s_coarse;
-    if (wide_records(plan)) {
-        fine_partition_body<true>(s, plan, g, c);
-    } else {
-        fine_partition_body<false>(s, plan, g, c);
+    const uint32_t first_tile = c << kFineBits;
+    const uint32_t in_range = arrived(plan.coarse_cursor + c * kCursorStride, plan.digit_room[c]);
+    const uint32_t begin = plan.tmp_start[c] + (g - plan.coarse_part_start[c]) * kPartTile;
+    const uint32_t end = min(begin + kPartTile, plan.tmp_start[c] + in_range);
+    if (begin >= end) return;                                 // uniform: room nobody needed
+    Record rec[kPartItems];
+    bool live[kPartItems];
+#pragma unroll
+    for (int i = 0; i < kPartItems; ++i) {
+        const uint32_t r = begin + i * kPartThreads + threadIdx.x;
+        live[i] = r < end;
+        rec[i] = live[i] ? unpack_tmp(plan.tmp[r], c) : Record{0u, 0};
     }
+    uint32_t *sorted = plan.sorted;
+    partition_step(
+        s, rec, live, [](uint32_t cell) { return (cell >> kTileBits) & (kFinePerCoarse - 1); },
+        [=](uint32_t f, uint32_t n, uint32_t &fits) {
+            const uint32_t tile = first_tile + f;
+            const uint32_t before = fetch_add_relaxed(plan.fine_cursor + tile * kCursorStride, n);
+            const uint32_t room = plan.tile_start[tile + 1] - plan.tile_start[tile];
+            fits = before < room ? room - before : 0u;
+            return plan.tile_start[tile] + before;
+        },
+        [](uint32_t, Record r) { return Staged{pack_sorted(r), 0u}; },
+        [=](uint32_t where, uint32_t word) { sorted[where] = word; },
+        [=](Record r) { add_relaxed(counts + r.cell, r.delta); });
 }
 
-// Accumulate: workgroup g takes up to kAccChunk records of one tile, sums them
-// into a private LDS image of the tile and merges the image into counts[].
+// Accumulate: workgroup g takes up to kAccChunk records of the room of one
+// tile, sums those that arrived there into a private LDS image of the tile and
+// merges the image into counts[].
 typedef int32_t i32x4 __attribute__((ext_vector_type(4)));
-#ifndef MLF_ACC_UNROLL
-#define MLF_ACC_UNROLL 4
-#endif
-constexpr int kAccUnroll = MLF_ACC_UNROLL;       // 128-bit record loads in flight per lane
+constexpr int kAccUnroll = 4;       // 128-bit record loads in flight per lane
 
 // Adds the records [begin, end) of one tile into its LDS image.  The records
-// are read with 128-bit loads (4 narrow or 2 wide records each), kAccUnroll of
-// them in flight per lane; the few records before the first and after the last
-// aligned group go one by one.
-template <bool WIDE>
-__device__ __forceinline__ void accumulate_records(int32_t *image, const void *__restrict__ sorted,
+// are read with 128-bit loads (4 records each), kAccUnroll of them in flight per
+// lane; the few records before the first and after the last aligned group go
+// one by one.
+__device__ __forceinline__ void accumulate_records(int32_t *image, const uint32_t *__restrict__ sorted,
                                                    uint32_t begin, uint32_t end)
 {
     typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-    constexpr uint32_t kPer = WIDE ? 2 : 4;
-    const uint32_t first = min((begin + kPer - 1) / kPer * kPer, end);
-    const uint32_t last = max(first, end / kPer * kPer);
+    const uint32_t first = min((begin + 3) / 4 * 4, end);
+    const uint32_t last = max(first, end / 4 * 4);
     auto add_one = [&](uint32_t r) {
-        const Record rec = load_sorted<WIDE>(sorted, r);
-        lds_add(&image[rec.cell], rec.delta);
+        const uint32_t v = sorted[r];
+        lds_add(&image[v & (kTileCells - 1)], static_cast<int32_t>(v) >> kTileBits);
     };
     if (threadIdx.x < first - begin) add_one(begin + threadIdx.x);
     if (threadIdx.x < end - last) add_one(last + threadIdx.x);
 
-    const u32x4 *groups = static_cast<const u32x4 *>(sorted);
-    const uint32_t g_end = last / kPer;
-    for (uint32_t g0 = first / kPer + threadIdx.x; g0 < g_end; g0 += kAccThreads * kAccUnroll) {
+    const u32x4 *groups = reinterpret_cast<const u32x4 *>(sorted);
+    const uint32_t g_end = last / 4;
+    for (uint32_t g0 = first / 4 + threadIdx.x; g0 < g_end; g0 += kAccThreads * kAccUnroll) {
         u32x4 x[kAccUnroll];
 #pragma unroll
         for (int u = 0; u < kAccUnroll; ++u) {
@@ -869,15 +915,10 @@ __device__ __forceinline__ void accumulate_records(int32_t *image, const void *_
 #pragma unroll
         for (int u = 0; u < kAccUnroll; ++u) {
             if (g0 + u * kAccThreads >= g_end) continue;
-            if constexpr (WIDE) {
-                lds_add(&image[x[u].x & (kTileCells - 1)], static_cast<int32_t>(x[u].y));
-                lds_add(&image[x[u].z & (kTileCells - 1)], static_cast<int32_t>(x[u].w));
-            } else {
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const uint32_t v = x[u][j];
-                    lds_add(&image[v & (kTileCells - 1)], static_cast<int32_t>(v) >> kTileBits);
-                }
+            for (int j = 0; j < 4; ++j) {
+                const uint32_t v = x[u][j];
+                lds_add(&image[v & (kTileCells - 1)], static_cast<int32_t>(v) >> kTileBits);
             }
         }
     }
@@ -909,13 +950,15 @@ __global__ __launch_bounds__(kAccThreads) void accumulate_kernel(int32_t *__rest
     __syncthreads();
     const uint32_t tile = s_tile;
     const uint32_t chunks = start[s_first + 1] - start[s_first];
+    // The hot tiles were filled by the coarse level (digit n_coarse + rank among
+    // the hot tiles), the others by the fine level.
+    const uint32_t *cursor = hot ? plan.coarse_cursor + (plan.n_coarse + s_first) * kCursorStride
+                                 : plan.fine_cursor + tile * kCursorStride;
+    const uint32_t in_tile = arrived(cursor, plan.tile_start[tile + 1] - plan.tile_start[tile]);
     const uint32_t begin = plan.tile_start[tile] + (g - start[s_first]) * kAccChunk;
-    const uint32_t end = min(begin + kAccChunk, plan.tile_start[tile + 1]);
-    if (wide_records(plan)) {
-        accumulate_records<true>(image, plan.sorted, begin, end);
-    } else {
-        accumulate_records<false>(image, plan.sorted, begin, end);
-    }
+    const uint32_t end = min(begin + kAccChunk, plan.tile_start[tile] + in_tile);
+    if (begin >= end) return;                                 // uniform: room nobody needed
+    accumulate_records(image, plan.sorted, begin, end);
     __syncthreads();
     const unsigned long long base = static_cast<unsigned long long>(tile) << kTileBits;
     const unsigned long long left = plan.n_cells - base;
@@ -962,22 +1005,10 @@ __global__ __launch_bounds__(kAccThreads) void accumulate_kernel(int32_t *__rest
 // one lane (no atomics on counts); the column sums go through the per-workgroup
 // LDS copy of the totals.
 // ---------------------------------------------------------------------------
-#ifndef MLF_DELTA_CHUNK
-#define MLF_DELTA_CHUNK 8
-#endif
-constexpr int kDeltaChunk = MLF_DELTA_CHUNK;   // delta matrices whose loads are in flight together
-#ifndef MLF_DELTA_VPT
-#define MLF_DELTA_VPT 2
-#endif
-constexpr int kDeltaVpt = MLF_DELTA_VPT;       // 128-bit groups per lane and step
-#ifndef MLF_DELTA_THREADS
-#define MLF_DELTA_THREADS 1024
-#endif
-constexpr int kDeltaThreads = MLF_DELTA_THREADS;   // lanes of a workgroup
-#ifndef MLF_DELTA_MAX_GRID
-#define MLF_DELTA_MAX_GRID 2048
-#endif
-constexpr unsigned kDeltaMaxGrid = MLF_DELTA_MAX_GRID;
+constexpr int kDeltaChunk = 8;              // delta matrices whose loads are in flight together
+constexpr int kDeltaVpt = 2;                // 128-bit groups per lane and step
+constexpr int kDeltaThreads = 1024;         // lanes of a workgroup
+constexpr unsigned kDeltaMaxGrid = 2048;    // workgroups of the persistent grid
 
 struct DeltaArgs {
     const int32_t *delta[MLF_MAX_K];
@@ -1094,16 +1125,38 @@ __global__ __launch_bounds__(kDeltaThreads) void dense_delta_kernel(const DeltaA
 
 size_t align_up(size_t x) { return (x + 255) & ~static_cast<size_t>(255); }
 
+// Words cleared before every call: sampled histogram and padded cursors.
+size_t zeroed_words(uint32_t n_tiles) { return n_tiles + static_cast<size_t>(kCursorStride) * (kMaxCoarse + n_tiles); }
+
 // Upper bounds of the work lists the plan kernel builds on the device: the sum
-// over ranges of ceil(n_r / step) is at most n / step + number of ranges.
-// Words cleared before every call: histogram, padded cursors, the format flag.
-size_t zeroed_words(uint32_t n_tiles, uint32_t n_coarse)
+// over groups of ceil(room_g / step) is at most slots / step + number of groups.
+size_t max_fine_steps(size_t slots, uint32_t n_coarse) { return slots / kPartTile + n_coarse; }
+size_t max_acc_items(size_t slots, uint32_t n_tiles) { return slots / kAccChunk + n_tiles; }
+
+// Every how many blocks of kSampleBlock triples one is sampled.
+long long sample_period(long long n, uint32_t n_tiles)
 {
-    return n_tiles + static_cast<size_t>(kCursorStride) * (kMaxCoarse + n_tiles) + 1;
+    long long period = n / (kSamplePerTile * static_cast<long long>(n_tiles));
+    if (period > kSampleMaxPeriod) period = kSampleMaxPeriod;
+    return period < 1 ? 1 : period;
 }
 
-size_t max_fine_steps(long long n, uint32_t n_coarse) { return static_cast<size_t>(n / kPartTile) + n_coarse; }
-size_t max_acc_items(long long n, uint32_t n_tiles) { return static_cast<size_t>(n / kAccChunk) + n_tiles; }
+// Words of tmp and of sorted: the rooms of all tiles add up to at most
+//   (S + kRoomSigmas * sqrt(tiles * S) + kRoomFloor * tiles) * n / S + tiles
+// for a sample of S triples (Cauchy-Schwarz on the square roots).  S is not
+// known here (it depends on how the triples are spread over the buffers), but
+// the bound falls as S grows, and S >= n / (2 * period): a buffer of m triples
+// has ceil(ceil(m / 256) / period) sampled blocks, all full but the last.
+size_t slots_for(long long n, uint32_t n_tiles, long long period)
+{
+    // (at least one sampled triple; a buffer shorter than one block is sampled whole)
+    const double least = n / (2.0 * static_cast<double>(period)) < 1.0 ? 1.0 : n / (2.0 * static_cast<double>(period));
+    const double tiles = n_tiles;
+    double bound = (least + kRoomSigmas * __builtin_sqrt(tiles * least) + kRoomFloor * tiles) * (n / least) + tiles;
+    bound = bound * 1.001 + 1024.0;                      // rounding of the kernel's binary32 arithmetic
+    const double most = 2147483647.0 - 1.0;              // indices keep bit 31 free
+    return static_cast<size_t>(bound < most ? bound : most);
+}
 
 // Whether the binned path can serve this shape, and its scratch layout.
 // Returns the scratch size in bytes (0 when the shape is not eligible).
@@ -1117,6 +1170,7 @@ size_t plan_layout(int32_t V, int32_t T, long long n, char *ws, BinPlan *plan)
     if (n < kMinBinnedTriples + kMinBinnedTriplesPerTile * n_tiles) return 0;
     const uint32_t n_coarse = (n_tiles + kFinePerCoarse - 1) >> kFineBits;
     if (n_coarse > kMaxCoarse) return 0;
+    const size_t n_slots = slots_for(n, n_tiles, sample_period(n, n_tiles));
     size_t off = 0;
     auto take = [&](size_t bytes) {
         char *p = ws != nullptr ? ws + off : nullptr;
@@ -1124,8 +1178,7 @@ size_t plan_layout(int32_t V, int32_t T, long long n, char *ws, BinPlan *plan)
         return p;
     };
     // hist, coarse_cursor, fine_cursor are contiguous: cleared by one kernel.
-    const size_t n_zeroed = zeroed_words(n_tiles, n_coarse);
-    char *hist = take(sizeof(uint32_t) * n_zeroed);
+    char *hist = take(sizeof(uint32_t) * zeroed_words(n_tiles));
     char *tile_start = take(sizeof(uint32_t) * (n_tiles + 1));
     char *coarse_part_start = take(sizeof(uint32_t) * (n_coarse + 1));
     char *chunk_start = take(sizeof(uint32_t) * (n_tiles + 1));
@@ -1133,15 +1186,15 @@ size_t plan_layout(int32_t V, int32_t T, long long n, char *ws, BinPlan *plan)
     char *hot_tile = take(sizeof(uint32_t) * kMaxCoarse);
     char *tmp_start = take(sizeof(uint32_t) * (n_coarse + 1));
     char *digit_start = take(sizeof(uint32_t) * kMaxCoarse);
+    char *digit_room = take(sizeof(uint32_t) * kMaxCoarse);
     char *hot_bits = take(sizeof(uint32_t) * (kHotWords + 1));
     char *hot_before = take(sizeof(uint32_t) * (kHotWords + 1));
-    char *tmp = take(sizeof(Record) * static_cast<size_t>(n));
-    char *sorted = take(sizeof(Record) * static_cast<size_t>(n));
+    char *tmp = take(sizeof(uint32_t) * n_slots);
+    char *sorted = take(sizeof(uint32_t) * n_slots);
     if (plan != nullptr) {
         plan->hist = reinterpret_cast<uint32_t *>(hist);
         plan->coarse_cursor = plan->hist + n_tiles;
         plan->fine_cursor = plan->coarse_cursor + static_cast<size_t>(kCursorStride) * kMaxCoarse;
-        plan->wide_flag = plan->fine_cursor + static_cast<size_t>(kCursorStride) * n_tiles;
         plan->tile_start = reinterpret_cast<uint32_t *>(tile_start);
         plan->coarse_part_start = reinterpret_cast<uint32_t *>(coarse_part_start);
         plan->chunk_start = reinterpret_cast<uint32_t *>(chunk_start);
@@ -1149,18 +1202,19 @@ size_t plan_layout(int32_t V, int32_t T, long long n, char *ws, BinPlan *plan)
         plan->hot_tile = reinterpret_cast<uint32_t *>(hot_tile);
         plan->tmp_start = reinterpret_cast<uint32_t *>(tmp_start);
         plan->digit_start = reinterpret_cast<uint32_t *>(digit_start);
+        plan->digit_room = reinterpret_cast<uint32_t *>(digit_room);
         plan->hot_bits = reinterpret_cast<uint32_t *>(hot_bits);
         plan->hot_before = reinterpret_cast<uint32_t *>(hot_before);
-        plan->tmp = tmp;
-        plan->sorted = sorted;
+        plan->tmp = reinterpret_cast<uint32_t *>(tmp);
+        plan->sorted = reinterpret_cast<uint32_t *>(sorted);
         plan->n_tiles = n_tiles;
         plan->n_coarse = n_coarse;
+        plan->n_slots = static_cast<uint32_t>(n_slots);
+        plan->per_sampled = 1.0f;
         plan->n_cells = cells;
     }
     return off;
 }
-
-bool launched() { return hipGetLastError() == hipSuccess; }
 
 }  // namespace
 
@@ -1204,62 +1258,83 @@ extern "C" mlf_status mlf_sparse_scatter_add(int32_t *counts, int32_t *totals, i
     a.rejected = n_rejected;
     a.V = V;
     a.T = T;
+    a.n_buffers = used;
+    a.sample_period = 1;
+    for (int k = 0; k <= MLF_MAX_K; ++k) a.step_start[k] = a.sample_start[k] = 0;
     hipStream_t s = static_cast<hipStream_t>(stream);
-
-    // The first pass over the triples: enough workgroups to fill the chip, few
-    // enough that their merges of private totals / histograms stay small next to
-    // the streamed triples.
-    long long per_buffer = (longest + kScanBlock * 16 - 1) / (kScanBlock * 16);
-    const long long cap = (kScanWorkgroups + used - 1) / used;
-    if (per_buffer > cap) per_buffer = cap;
-    if (per_buffer < 1) per_buffer = 1;
-    const dim3 scan_grid(static_cast<unsigned>(per_buffer), static_cast<unsigned>(used));
-    bool lds_totals = totals != nullptr && T <= kMaxLdsTopics;
-    size_t totals_lds = lds_totals ? static_cast<size_t>(T) * sizeof(int32_t) : 0;
 
     BinPlan plan = {};
     const size_t need = plan_layout(V, T, total, static_cast<char *>(workspace), &plan);
     const bool binned = need != 0 && workspace != nullptr && workspace_bytes >= need &&
                         reinterpret_cast<uintptr_t>(workspace) % 256 == 0;
     if (!binned) {
-        if (lds_totals) {
-            scan_triples_kernel<false, true><<<scan_grid, dim3(kScanBlock), totals_lds, s>>>(a, plan);
-        } else {
-            scan_triples_kernel<false, false><<<scan_grid, dim3(kScanBlock), 0, s>>>(a, plan);
-        }
-        return launched() ? MLF_OK : MLF_EHIP;
+        // Enough workgroups to fill the chip, few enough that their merges of
+        // private totals stay small next to the streamed triples.
+        long long per_buffer = (longest + kScanBlock * 16 - 1) / (kScanBlock * 16);
+        const long long cap = (kScanWorkgroups + used - 1) / used;
+        if (per_buffer > cap) per_buffer = cap;
+        if (per_buffer < 1) per_buffer = 1;
+        const dim3 grid(static_cast<unsigned>(per_buffer), static_cast<unsigned>(used));
+        const bool lds_totals = totals != nullptr && T <= kMaxLdsTopics;
+        const bool ok = lds_totals ? launch_kernel(direct_kernel<true>, grid, dim3(kScanBlock),
+                                                   static_cast<size_t>(T) * sizeof(int32_t), s, a)
+                                   : launch_kernel(direct_kernel<false>, grid, dim3(kScanBlock), 0, s, a);
+        return ok ? MLF_OK : MLF_EHIP;
     }
 
-    // 1. clear the counters, 2. histogram (+ totals, rejects), 3. offsets,
-    // 4. coarse partition, 5. fine partition, 6. accumulate and merge.
-    const uint32_t n_clear = static_cast<uint32_t>(zeroed_words(plan.n_tiles, plan.n_coarse));
-    clear_kernel<<<dim3((n_clear + kThreads - 1) / kThreads), dim3(kThreads), 0, s>>>(plan.hist, n_clear);
-    if (!launched()) return MLF_EHIP;
-    const size_t hist_lds = static_cast<size_t>(plan.n_tiles) * sizeof(uint32_t);
-    if (totals_lds + hist_lds <= 65536) {
-        if (lds_totals) {
-            scan_triples_kernel<true, true><<<scan_grid, dim3(kScanBlock), totals_lds + hist_lds, s>>>(a, plan);
-        } else {
-            scan_triples_kernel<true, false><<<scan_grid, dim3(kScanBlock), hist_lds, s>>>(a, plan);
-        }
-    } else if (lds_totals && T <= kBigTopics) {
-        // More than 64 KiB of histogram and totals: the variant with a static array.
-        scan_triples_kernel<true, true, true><<<scan_grid, dim3(kScanBlock), 0, s>>>(a, plan);
-    } else {
-        scan_triples_kernel<true, false, true><<<scan_grid, dim3(kScanBlock), 0, s>>>(a, plan);
+    // The sample and the steps of the coarse level.
+    const long long period = sample_period(total, plan.n_tiles);
+    a.sample_period = static_cast<int>(period);
+    long long sampled = 0;
+    for (int k = 0; k < used; ++k) {
+        const long long m = a.n_triples[k];
+        const long long blocks = (m + kSampleBlock - 1) / kSampleBlock;
+        const long long picked = (blocks + period - 1) / period;          // blocks 0, period, 2 period, ...
+        const long long last = (picked - 1) * period;                     // the last one may be short
+        sampled += (picked - 1) * kSampleBlock + (m - last * kSampleBlock < kSampleBlock ? m - last * kSampleBlock : kSampleBlock);
+        a.step_start[k + 1] = a.step_start[k] + static_cast<uint32_t>((m + kPartTile - 1) / kPartTile);
+        a.sample_start[k + 1] = a.sample_start[k] + static_cast<uint32_t>(picked);
     }
-    if (!launched()) return MLF_EHIP;
-    plan_kernel<<<dim3(1), dim3(kPlanThreads), 0, s>>>(plan);
-    if (!launched()) return MLF_EHIP;
-    const unsigned steps_per_buffer = static_cast<unsigned>((longest + kPartTile - 1) / kPartTile);
-    coarse_partition_kernel<<<dim3(steps_per_buffer, static_cast<unsigned>(used)), dim3(kPartThreads), 0, s>>>(a, plan);
-    if (!launched()) return MLF_EHIP;
-    const unsigned fine_steps = static_cast<unsigned>(max_fine_steps(total, plan.n_coarse));
-    fine_partition_kernel<<<dim3(fine_steps), dim3(kPartThreads), 0, s>>>(plan);
-    if (!launched()) return MLF_EHIP;
-    const unsigned acc_items = static_cast<unsigned>(max_acc_items(total, plan.n_tiles));
-    accumulate_kernel<<<dim3(acc_items), dim3(kAccThreads), 0, s>>>(counts, plan);
-    return launched() ? MLF_OK : MLF_EHIP;
+    for (int k = used + 1; k <= MLF_MAX_K; ++k) {
+        a.step_start[k] = a.step_start[used];
+        a.sample_start[k] = a.sample_start[used];
+    }
+    plan.per_sampled = static_cast<float>(static_cast<double>(total) / static_cast<double>(sampled));
+
+    // 1. clear the counters, 2. sample histogram, 3. room and offsets,
+    // 4. coarse partition (+ totals, rejects), 5. fine partition, 6. accumulate and merge.
+    const uint32_t n_clear = static_cast<uint32_t>(zeroed_words(plan.n_tiles));
+    if (!launch_kernel(clear_kernel, dim3((n_clear + kThreads - 1) / kThreads), dim3(kThreads), 0, s,
+                       plan.hist, n_clear)) {
+        return MLF_EHIP;
+    }
+    const size_t hist_lds = static_cast<size_t>(plan.n_tiles) * sizeof(uint32_t);
+    const long long per_workgroup = (kScanBlock / kSampleBlock) * kSampleUnroll;
+    long long sample_grid = (a.sample_start[used] + per_workgroup - 1) / per_workgroup;
+    if (sample_grid > kSampleWorkgroups) sample_grid = kSampleWorkgroups;
+    if (sample_grid < 1) sample_grid = 1;
+    const bool sampled_ok =
+        hist_lds <= 65536 ? launch_kernel(sample_kernel<false>, dim3(static_cast<unsigned>(sample_grid)),
+                                          dim3(kScanBlock), hist_lds, s, a, plan)
+                          : launch_kernel(sample_kernel<true>, dim3(static_cast<unsigned>(sample_grid)),
+                                          dim3(kScanBlock), 0, s, a, plan);
+    if (!sampled_ok) return MLF_EHIP;
+    if (!launch_kernel(plan_kernel, dim3(1), dim3(kPlanThreads), 0, s, plan)) return MLF_EHIP;
+    const uint32_t n_steps = a.step_start[used];
+    const unsigned coarse_grid = n_steps < kCoarseWorkgroups ? n_steps : kCoarseWorkgroups;
+    const size_t hot_lds = static_cast<size_t>((plan.n_tiles + 31) / 32) * 2 * sizeof(uint32_t);
+    const bool lds_totals = totals != nullptr && T <= kCoarseLdsTopics;
+    const bool coarse_ok =
+        lds_totals ? launch_kernel(coarse_partition_kernel<true>, dim3(coarse_grid), dim3(kPartThreads),
+                                   hot_lds + static_cast<size_t>(T) * sizeof(int32_t), s, a, plan)
+                   : launch_kernel(coarse_partition_kernel<false>, dim3(coarse_grid), dim3(kPartThreads),
+                                   hot_lds, s, a, plan);
+    if (!coarse_ok) return MLF_EHIP;
+    const unsigned fine_steps = static_cast<unsigned>(max_fine_steps(plan.n_slots, plan.n_coarse));
+    if (!launch_kernel(fine_partition_kernel, dim3(fine_steps), dim3(kPartThreads), 0, s, counts, plan)) return MLF_EHIP;
+    const unsigned acc_items = static_cast<unsigned>(max_acc_items(plan.n_slots, plan.n_tiles));
+    if (!launch_kernel(accumulate_kernel, dim3(acc_items), dim3(kAccThreads), 0, s, counts, plan)) return MLF_EHIP;
+    return MLF_OK;
 }
 
 extern "C" mlf_status mlf_counts_add_dense(int32_t *counts, int32_t *totals, int32_t V, int32_t T,
@@ -1295,11 +1370,10 @@ extern "C" mlf_status mlf_counts_add_dense(int32_t *counts, int32_t *totals, int
     if (tiles > kDeltaMaxGrid) tiles = kDeltaMaxGrid;
     if (tiles < 1) tiles = 1;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (totals != nullptr && T <= kMaxLdsTopics) {
-        dense_delta_kernel<true><<<dim3(static_cast<unsigned>(tiles)), dim3(kDeltaThreads),
-                                   static_cast<size_t>(T) * sizeof(int32_t), s>>>(a);
-    } else {
-        dense_delta_kernel<false><<<dim3(static_cast<unsigned>(tiles)), dim3(kDeltaThreads), 0, s>>>(a);
-    }
-    return launched() ? MLF_OK : MLF_EHIP;
+    const bool ok = totals != nullptr && T <= kMaxLdsTopics
+                        ? launch_kernel(dense_delta_kernel<true>, dim3(static_cast<unsigned>(tiles)),
+                                        dim3(kDeltaThreads), static_cast<size_t>(T) * sizeof(int32_t), s, a)
+                        : launch_kernel(dense_delta_kernel<false>, dim3(static_cast<unsigned>(tiles)),
+                                        dim3(kDeltaThreads), 0, s, a);
+    return ok ? MLF_OK : MLF_EHIP;
 }

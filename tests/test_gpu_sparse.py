@@ -96,6 +96,47 @@ def test_matrices_at_the_binned_paths_upper_limit(V, T):
     torch.cuda.empty_cache()
 
 
+def _misleading_batch(V, T, K, m, sampled_word_hi, other_word_lo, other_word_hi, seed):
+    """Triples whose sampled blocks (every p-th block of 256, p as the header
+    states) hit words below `sampled_word_hi` only, while all other blocks hit
+    words in [other_word_lo, other_word_hi): the plan made from the sample is
+    wrong about the rest of the batch."""
+    tiles = (V * T + 32767) // 32768
+    period = max(1, min(64, (K * m) // (256 * tiles)))
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+    out = []
+    for _ in range(K):
+        block = torch.arange(m, device="cuda") // 256
+        sampled = (block % period) == 0
+        lo = torch.where(sampled, 0, other_word_lo)
+        hi = torch.where(sampled, sampled_word_hi, other_word_hi)
+        word = lo + (torch.rand(m, generator=g, device="cuda") * (hi - lo)).long().clamp_(max=V - 1)
+        topic = torch.randint(0, T, (m,), generator=g, device="cuda")
+        delta = torch.randint(0, 2, (m,), generator=g, device="cuda") * 2 - 1
+        out.append(torch.stack([word, topic, delta], dim=1).to(torch.int32).contiguous())
+    return out
+
+
+@pytest.mark.parametrize("case", ["sample concentrated, bulk spread", "sample spread, bulk concentrated"])
+def test_plan_made_from_a_misleading_sample(case):
+    """The groups' room comes from a sample; records that find their group full
+    are added to counts[] directly.  Here the sample is as wrong as it can be, at
+    the coarse level (first case) and at both levels (second case: the bulk goes
+    to a few tiles of one coarse range that the sample saw as lightly used), and
+    the result must still equal the oracle's in every cell."""
+    V, T, K, m = 160_000, 257, 2, 1_500_000               # 1,255 tiles, 10 coarse ranges
+    cfg = recipe(V=V, T=T, K=K, m=m)
+    assert mlf.mlf_sparse_workspace_bytes(V, T, K * m) > 0
+    if case.startswith("sample concentrated"):
+        triples = _misleading_batch(V, T, K, m, 100, 0, V, seed=1)
+    else:
+        triples = _misleading_batch(V, T, K, m, V, 40_000, 40_300, seed=2)
+    d = W.sparse_inputs(recipe(V=V, T=T, K=1, m=8), "cuda", init="random")
+    d["triples"] = triples
+    run_sparse(cfg, d, True)
+
+
 @pytest.mark.parametrize("use_workspace", [False, True])
 def test_hand_case_ragged_buffers_and_optional_arguments(use_workspace, golden):
     g = {k: np.array([int(x) for x in v], dtype=np.int32)

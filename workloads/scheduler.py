@@ -8,20 +8,21 @@ drops -- the final ordering algorithm, Alg. 2), so that tests and benchmarks
 can also run on sequences with that structure.  It is control-plane code on the
 CPU and contains none of the arithmetic of the GPU path.
 
-Network model (the paper defines the completion time t_en and the bandwidth
-reservation NetUp by two figures that its text does not contain; this is the
-reading used here, and it reproduces the worked example of Sec. 5.1.3):
+Network model (the paper defines the completion time t_en of a transfer and the
+reservation of its bandwidth by two figures that its text does not contain; this
+is the reading used here, and it reproduces the worked example of Sec. 5.1.3):
 
   * one server; worker j reaches it over its own access link and the server's
     link; each link has a residual bandwidth that is piecewise constant in time;
   * an update of `size` available at t = 0 uses, at every instant, all of the
     bottleneck residual min(access_j(t), server(t)); t_en is the instant its
     bytes are through;
-  * NetUp reserves exactly that time-varying rate on both links until t_en.
+  * committing a transfer reserves exactly that time-varying rate on both links
+    until t_en.
 
-Deadlines: dl(g) = v(g) + tau_max - v_init, compared with the iteration counter
-of the ordering loop as the algorithm is printed (the counter also advances when
-an update is dropped).  An update whose deadline has passed counts as due.
+Deadlines: dl(g) = v(g) + tau_max - v_init counts commit slots: every update
+that is considered takes one slot, also when it ends up dropped.  An update
+whose deadline slot has been reached or passed is due.
 """
 from __future__ import annotations
 
@@ -72,7 +73,8 @@ def completion_time(path: Profile, size: float) -> float:
 
 
 def reserve(link: Profile, used: Profile, until: float) -> Profile:
-    """NetUp on one link: subtract `used` (the transfer's rate) on [0, until)."""
+    """One link after a transfer is committed: `used` (the transfer's rate) is
+    taken off on [0, until)."""
     times = sorted(set(link.t) | set(used.t) | ({until} if until < INF else set()))
     rl, ru = link.at_breaks(times), used.at_breaks(times)
     rate = [max(l - (u if t < until else 0.0), 0.0) for t, l, u in zip(times, rl, ru)]
@@ -98,46 +100,70 @@ class Network:
         return completion_time(self.path(g), g.size)
 
     def after(self, g: Update) -> "Network":
-        """NetUp(NW, g, S): the network with g's transfer reserved."""
+        """The network with g's transfer reserved on its access link and on the
+        server link."""
         used, end = self.path(g), self.t_en(g)
         access = dict(self.access)
         access[g.worker] = reserve(self.access[g.worker], used, end)
         return Network(reserve(self.server, used, end), access)
 
 
-def _pick(iteration, pending, nw, deadline):
-    """ShrtDline: a due update if there is one (the one finishing first among
-    several), else the update with the least completion time."""
-    if not pending:
-        return None
-    due = [g for g in pending if deadline[g.worker] <= iteration]
-    pool = due if due else pending
-    return min(pool, key=lambda g: (nw.t_en(g), g.worker))
+class CommitRound:
+    """One pass of the final ordering (Sec. 5.1, Alg. 2) over a batch: the
+    updates still waiting, the residual network after the commits so far, and
+    the commit slot being filled."""
+
+    def __init__(self, updates, nw: Network, tau_max: int, v_init: int):
+        self.waiting = {g.worker: g for g in updates}
+        self.deadline = {g.worker: g.version + tau_max - v_init for g in updates}
+        self.nw = nw
+        self.slot = 1
+        self.order, self.dropped = [], []
+
+    def front_runner(self, slot, nw, skip=None):
+        """The update that would take `slot` on network `nw`: among the due ones
+        if any is due, else among all that wait, the one whose transfer ends
+        first (ties by worker id).  `skip` leaves one worker out."""
+        pool = [g for w, g in self.waiting.items() if w != skip]
+        if not pool:
+            return None
+        due = [g for g in pool if self.deadline[g.worker] <= slot]
+        return min(due or pool, key=lambda g: (nw.t_en(g), g.worker))
+
+    def overtaken(self, chosen, reserved):
+        """Look-ahead: with `chosen` reserved, would the front runner of the
+        next slot still be through before `chosen` itself?  Then `chosen` holds
+        nobody up by being dropped at its worker (the 10 s / 1.1 s example of
+        Sec. 5.1.3)."""
+        rival = self.front_runner(self.slot + 1, reserved, skip=chosen.worker)
+        return rival is not None and self.nw.t_en(chosen) > reserved.t_en(rival)
+
+    def fill_slot(self):
+        chosen = self.front_runner(self.slot, self.nw)
+        reserved = self.nw.after(chosen)
+        if self.overtaken(chosen, reserved):
+            self.dropped.append(chosen.worker)
+        else:
+            self.order.append(chosen.worker)
+            self.nw = reserved
+        del self.waiting[chosen.worker]
+        self.slot += 1
 
 
 def order_updates(updates, nw: Network, tau_max: int, v_init: int):
-    """Final ordering algorithm (Alg. 2).  Returns (order, dropped): the workers
-    in commit order, and the workers whose updates were dropped."""
-    deadline = {g.worker: g.version + tau_max - v_init for g in updates}
-    pending = list(updates)
-    order, dropped = [], []
-    for i in range(1, len(updates) + 1):
-        current = _pick(i, pending, nw, deadline)
-        if current is None:
-            break
-        pending = [g for g in pending if g.worker != current.worker]
-        reserved = nw.after(current)
-        nxt = _pick(i + 1, pending, reserved, deadline)
-        if nxt is not None and nw.t_en(current) > reserved.t_en(nxt):
-            dropped.append(current.worker)       # "next" would be applied first: drop
-            continue
-        order.append(current.worker)
-        nw = reserved
-    return order, dropped
+    """Final ordering of a batch (Sec. 5.1, Alg. 2): deadline-forced updates
+    first, else the shortest transfer, with the look-ahead drop.  Returns
+    (order, dropped): the workers in commit order, and the workers whose updates
+    were dropped."""
+    rnd = CommitRound(updates, nw, tau_max, v_init)
+    while rnd.waiting:
+        rnd.fill_slot()
+    return rnd.order, rnd.dropped
 
 
 def shortest_transfer_first(updates, nw: Network):
-    """Alg. 1: greedy shortest-completion-time ordering without deadlines."""
+    """Ordering without deadlines (Sec. 5.1, Alg. 1): always the transfer that
+    ends first on what is left of the network."""
     pending, order, finish = list(updates), [], []
     while pending:
         g = min(pending, key=lambda u: (nw.t_en(u), u.worker))
@@ -151,7 +177,7 @@ def shortest_transfer_first(updates, nw: Network):
 def scheduled_order(K: int, seed: int, size: float = 100e6, tau_max=None):
     """A seeded batch of K equal-sized updates on a cluster shaped like the
     paper's (Sec. 6: 10 Gbps links; some workers behind slow links, some updates
-    stale) run through Alg. 2.  Returns an int32 order (dropped workers left out),
+    stale) run through the final ordering.  Returns an int32 order (dropped workers left out),
     the form the GPU calls take."""
     rng = np.random.default_rng(seed)
     server = Profile.constant(10e9 / 8)
