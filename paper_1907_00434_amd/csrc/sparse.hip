@@ -729,9 +729,14 @@ __device__ __forceinline__ void partition_step(PartitionLds &s, const Record (&r
 // to plan.tmp, grouped by coarse range.  A record whose group is full, and a
 // triple whose delta is too large for a record, is added to counts[] at once.
 // Dynamic LDS: [hot-tile table: 2 words per 32 tiles][T totals if LDS_TOTALS].
+//
+// Two workgroups share a CU (the grid is two per CU): while one waits for its
+// triples or for a barrier the other works.  That takes 8 wavefronts per SIMD,
+// i.e. at most 64 vector registers; the cap costs three spilled values and buys
+// 11 % of the kernel's time against one workgroup per CU.
 template <bool LDS_TOTALS>
-__global__ __launch_bounds__(kPartThreads) void coarse_partition_kernel(const SparseArgs a,
-                                                                    const BinPlan plan)
+__global__ __launch_bounds__(kPartThreads) __attribute__((amdgpu_waves_per_eu(8, 8)))
+void coarse_partition_kernel(const SparseArgs a, const BinPlan plan)
 {
     extern __shared__ uint32_t coarse_lds[];
     __shared__ PartitionLds s;
