@@ -49,7 +49,6 @@ constexpr int kFineBits = 7;                     // log2 of the fine tiles per c
 constexpr uint32_t kFinePerCoarse = 1u << kFineBits;
 constexpr uint32_t kMaxCoarse = 256;             // digits of the coarse level (one counter per lane)
 constexpr uint32_t kMaxTiles = 32768;            // tiles a call may span (LDS histogram, plan tables)
-constexpr uint32_t kHotWords = kMaxTiles / 32;   // words of the hot-tile bitmap
 constexpr int kPartThreads = 1024;               // lanes of a partition workgroup
 constexpr int kPartItems = 8;                    // records per lane in a partition step
 constexpr uint32_t kPartTile = kPartThreads * kPartItems;      // records per step
@@ -96,38 +95,25 @@ struct SparseArgs {
     int sample_period;                   // every sample_period-th block of kSampleBlock triples is sampled
 };
 
-// A triple reduced to what the binned path needs: flat cell index and delta.
-struct Record {
-    uint32_t cell;
-    int32_t delta;
-};
-
-// Records travel through the scratch as ONE word.  Between the two partition
-// levels the coarse range is implied by where the record lies, which leaves
-// kCoarseShift bits of cell index and the rest for the delta; after the fine
-// level only the kTileBits cell bits inside the tile are needed.  LDA deltas are
+// Records travel through the scratch as ONE word, the same at every stage: the
+// low kCoarseShift bits are the cell index inside the record's coarse range (the
+// range itself is implied by where the record lies: its group in `tmp`, its
+// tile in `sorted`), the bits above are the delta.  The low kTileBits bits are the
+// cell inside the tile, which is all the accumulate step needs.  LDA deltas are
 // almost always +-1.  A delta outside [-kSmallDeltaLimit, kSmallDeltaLimit)
 // never becomes a record: the coarse level adds it to counts[] with a global
 // atomic instead, which costs what the direct path costs for that triple.  A
-// zero delta changes nothing and is dropped.
+// zero delta changes nothing and is dropped, so a record word is never 0.
 constexpr int kCoarseShift = kTileBits + kFineBits;
+constexpr uint32_t kRangeMask = (1u << kCoarseShift) - 1;
 constexpr int32_t kSmallDeltaLimit = 1 << (31 - kCoarseShift);
 
-__device__ __forceinline__ uint32_t pack_tmp(Record r)
+__device__ __forceinline__ uint32_t pack_record(uint32_t cell, int32_t delta)
 {
-    return (r.cell & ((1u << kCoarseShift) - 1)) | (static_cast<uint32_t>(r.delta) << kCoarseShift);
+    return (cell & kRangeMask) | (static_cast<uint32_t>(delta) << kCoarseShift);
 }
 
-__device__ __forceinline__ Record unpack_tmp(uint32_t v, uint32_t coarse)
-{
-    return Record{(coarse << kCoarseShift) | (v & ((1u << kCoarseShift) - 1)),
-                  static_cast<int32_t>(v) >> kCoarseShift};
-}
-
-__device__ __forceinline__ uint32_t pack_sorted(Record r)
-{
-    return (r.cell & (kTileCells - 1)) | (static_cast<uint32_t>(r.delta) << kTileBits);
-}
+__device__ __forceinline__ int32_t record_delta(uint32_t v) { return static_cast<int32_t>(v) >> kCoarseShift; }
 
 // Control block of the binned path, carved out of the caller's scratch.  All
 // the "start" tables describe ROOM (planned from the sample); how many records
@@ -145,13 +131,15 @@ struct BinPlan {
                                   //             tiles' items come first in the launch
     uint32_t *hot_tile;           // [kMaxCoarse] tile of each hot digit
     uint32_t *tmp_start;          // [n_coarse+1] where each coarse range's room begins in `tmp`
-    uint32_t *digit_start;        // [kMaxCoarse] first output index of each digit of the coarse level:
-                                  //              in tmp for a coarse range, in sorted for a hot tile
+    uint32_t *digit_start;        // [kMaxCoarse] first output index of each digit of the coarse level,
+                                  //              counted from tmp[0]: in tmp for a coarse range, in
+                                  //              sorted (sorted_base + ...) for a hot tile
     uint32_t *digit_room;         // [kMaxCoarse] room of each digit of the coarse level
-    uint32_t *hot_bits;           // [kHotWords] bit b set = tile b is hot
-    uint32_t *hot_before;         // [kHotWords] hot tiles before the first tile of each word
+    uint8_t *tile_digit;          // [n_tiles] digit of each tile at the coarse level: its coarse range,
+                                  //              or n_coarse + its rank among the hot tiles
     uint32_t *tmp;                // [n_slots] records grouped by coarse range
-    uint32_t *sorted;             // [n_slots] records grouped by tile
+    uint32_t *sorted;             // [n_slots] records grouped by tile; sorted = tmp + sorted_base
+    uint32_t sorted_base;
     uint32_t n_tiles;
     uint32_t n_coarse;
     uint32_t n_slots;             // words in tmp and in sorted
@@ -200,28 +188,61 @@ __device__ __forceinline__ uint32_t broadcast(uint32_t v, int lane)
         __builtin_amdgcn_readlane(static_cast<int>(v), __builtin_amdgcn_readfirstlane(lane)));
 }
 
-// counter[bin] += 1 for every live lane, returning to each the value it would
-// have seen had the lanes gone one by one (its rank in the bin).  Skewed data
-// puts most lanes of a wavefront into one bin, and LDS atomics on one address
-// are served one lane at a time; so the lanes that share the bin of the first
-// live lane are counted with a ballot and added by a single atomic, and only
-// the others go one by one.  Must be called by whole wavefronts.
-__device__ __forceinline__ uint32_t wave_rank(uint32_t *counter, uint32_t bin, bool live)
+// Inclusive prefix sum over the 64 lanes of a wavefront with cross-lane moves of
+// the vector pipeline (no LDS): shifts by 1, 2, 4 and 8 inside each row of 16
+// lanes (a lane without a source adds 0), then the last lane of rows 0 and 2
+// into rows 1 and 3, then lane 31 into rows 2 and 3.
+__device__ __forceinline__ uint32_t wave_inclusive_sum(uint32_t v)
 {
-    const unsigned long long live_mask = __ballot(live);
-    if (live_mask == 0) return 0;                                   // uniform
-    const int leader = __ffsll(static_cast<long long>(live_mask)) - 1;
-    const uint32_t lead_bin = broadcast(bin, leader);
-    const bool grouped = live && bin == lead_bin;
-    const unsigned long long group = __ballot(grouped);
-    uint32_t base = 0;
-    if (static_cast<int>(threadIdx.x & 63) == leader) {
-        // (indexed by the lane's own bin, which equals lead_bin here)
-        base = lds_fetch_add(&counter[bin], static_cast<uint32_t>(__popcll(group)));
+    v += __builtin_amdgcn_update_dpp(0u, v, 0x111, 0xf, 0xf, false);     // row_shr:1
+    v += __builtin_amdgcn_update_dpp(0u, v, 0x112, 0xf, 0xf, false);     // row_shr:2
+    v += __builtin_amdgcn_update_dpp(0u, v, 0x114, 0xf, 0xf, false);     // row_shr:4
+    v += __builtin_amdgcn_update_dpp(0u, v, 0x118, 0xf, 0xf, false);     // row_shr:8
+    v += __builtin_amdgcn_update_dpp(0u, v, 0x142, 0xa, 0xf, false);     // row_bcast:15 into rows 1, 3
+    v += __builtin_amdgcn_update_dpp(0u, v, 0x143, 0xc, 0xf, false);     // row_bcast:31 into rows 2, 3
+    return v;
+}
+
+// For each of the N records of every lane: counter[bin[i]] += 1 if live[i], and
+// rank[i] = the value the record would have seen had the records gone one by one
+// (its rank in its bin; no two live records of a bin get the same).  Skewed data
+// puts many lanes of a wavefront into one bin, and LDS atomics on one address
+// are served one lane at a time; so for every i the lanes that share the bin of
+// the first live lane are counted with a ballot and added by that lane alone,
+// and only the others add for themselves: one LDS atomic instruction per i (the
+// group's other members sit it out).  The N atomics of a lane are issued back to
+// back and waited for once, so that their trips through the LDS overlap: with
+// two 16-wavefront workgroups on a CU a single trip takes several hundred
+// cycles.  Must be called by whole wavefronts.
+template <int N>
+__device__ __forceinline__ void wave_rank_all(uint32_t *counter, const uint32_t (&bin)[N],
+                                              const bool (&live)[N], uint32_t (&rank)[N])
+{
+    const int lane = static_cast<int>(threadIdx.x & 63);
+    unsigned long long group[N];
+    int first[N];
+    bool grouped[N];
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+        const unsigned long long live_mask = __ballot(live[i]);
+        // (with no live lane the lookups read lane 63: harmless, nobody is grouped then)
+        first[i] = (__ffsll(static_cast<long long>(live_mask)) - 1) & 63;          // uniform
+        grouped[i] = live[i] && bin[i] == broadcast(bin[i], first[i]);
+        group[i] = __ballot(grouped[i]);
     }
-    base = broadcast(base, leader);
-    if (grouped) return base + lanes_below(group);
-    return live ? lds_fetch_add(&counter[bin], 1u) : 0u;
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+        rank[i] = 0;
+        if (live[i] && (!grouped[i] || lane == first[i])) {
+            rank[i] = lds_fetch_add(&counter[bin[i]],
+                                    grouped[i] ? static_cast<uint32_t>(__popcll(group[i])) : 1u);
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+        const uint32_t base = broadcast(rank[i], first[i]);
+        if (grouped[i]) rank[i] = base + lanes_below(group[i]);
+    }
 }
 
 // counter[bin] += 1 for every active lane, with the same grouping of the lanes
@@ -248,6 +269,21 @@ __device__ __forceinline__ bool load_triple(const int32_t *tr, long long r, int 
     word = __builtin_nontemporal_load(tr + 3 * r);
     topic = __builtin_nontemporal_load(tr + 3 * r + 1);
     delta = __builtin_nontemporal_load(tr + 3 * r + 2);
+    return static_cast<unsigned>(word) < static_cast<unsigned>(V) &&
+           static_cast<unsigned>(topic) < static_cast<unsigned>(T);
+}
+
+// The same for the triple that starts `offset` bytes after `base` (a wavefront-
+// uniform address plus a 32-bit lane offset: one 96-bit load).
+__device__ __forceinline__ bool load_triple_at(const char *base, uint32_t offset, int V, int T,
+                                               int &word, int &topic, int &delta)
+{
+    typedef int32_t i32x3 __attribute__((ext_vector_type(3)));
+    typedef i32x3 __attribute__((aligned(4))) i32x3_unaligned;
+    const i32x3 v = __builtin_nontemporal_load(reinterpret_cast<const i32x3_unaligned *>(base + offset));
+    word = v.x;
+    topic = v.y;
+    delta = v.z;
     return static_cast<unsigned>(word) < static_cast<unsigned>(V) &&
            static_cast<unsigned>(topic) < static_cast<unsigned>(T);
 }
@@ -450,9 +486,8 @@ __device__ __forceinline__ void block_scan(const uint32_t (&v)[N], uint32_t (&ex
 // tiles hold most of the records, so most records are moved once instead of
 // twice.  The hot tiles are those with at least `threshold` sampled triples,
 // the smallest power-of-two fraction of the sample that leaves no more hot tiles
-// than spare digits.  They are published as a bitmap plus, per bitmap word, the
-// number of hot tiles before it, so that a lane finds the digit of a tile with
-// one LDS read and a population count.
+// than spare digits.  The digit of every tile (its coarse range, or n_coarse +
+// its rank among the hot tiles) is published as a table of one byte per tile.
 //
 // Lane i looks after the tiles i, i + kPlanThreads, ... (one per round); the
 // rooms are kept in LDS, and every table over the tiles is a running block scan
@@ -531,8 +566,8 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const BinPlan plan)
     __syncthreads();
     const uint32_t threshold = s_threshold;
 
-    // Hot tiles: bitmap (the words that cover the call's tiles), digit of each
-    // (its rank among the hot tiles), hot room per coarse range; and the
+    // Hot tiles: digit of each (its rank among the hot tiles), hot room per
+    // coarse range, the digit of every tile; and the
     // accumulate work items (kAccChunk records of room each) of the tiles that
     // are not hot.
     uint32_t n_hot = 0, n_items = 0;
@@ -542,30 +577,24 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const BinPlan plan)
         const uint32_t sampled = b < n_tiles ? plan.hist[b] : 0u;
         const uint32_t mine = room[b];
         const bool hot = sampled != 0 && sampled >= threshold;
-        const unsigned long long mask = __ballot(hot);
-        if (lane == 0) {
-            plan.hot_bits[b >> 5] = static_cast<uint32_t>(mask);
-            plan.hot_bits[(b >> 5) + 1] = static_cast<uint32_t>(mask >> 32);
-        }
         const uint32_t v[2] = {hot ? 1u : 0u, hot ? 0u : (mine + kAccChunk - 1) / kAccChunk};
         uint32_t e[2], t[2];
         block_scan<2>(v, e, t, wave_sums);
         const uint32_t slot = n_hot + e[0];
-        if ((threadIdx.x & 31) == 0) plan.hot_before[b >> 5] = slot;
         if (hot) {
             plan.hot_tile[slot] = b;
-            plan.digit_start[n_coarse + slot] = plan.tile_start[b];      // this lane wrote it
+            plan.digit_start[n_coarse + slot] = plan.sorted_base + plan.tile_start[b];      // this lane wrote it
             plan.digit_room[n_coarse + slot] = mine;
             lds_fetch_add(&hot_in_range[b >> kFineBits], mine);
         }
-        if (b < n_tiles) plan.chunk_start[b] = n_items + e[1];
+        if (b < n_tiles) {
+            plan.chunk_start[b] = n_items + e[1];
+            plan.tile_digit[b] = static_cast<uint8_t>(hot ? n_coarse + slot : b >> kFineBits);
+        }
         n_hot += t[0];
         n_items += t[1];
     }
-    if (threadIdx.x == 0) {
-        plan.hot_before[kHotWords] = n_hot;
-        plan.chunk_start[n_tiles] = n_items;
-    }
+    if (threadIdx.x == 0) plan.chunk_start[n_tiles] = n_items;
     __syncthreads();
     __threadfence_block();
 
@@ -624,101 +653,121 @@ __device__ __forceinline__ uint32_t owner_of(const uint32_t *start, uint32_t n, 
     return lo;
 }
 
-// One partition step of a workgroup: up to kPartTile records held in registers
-// are grouped by digit (< kMaxCoarse) in LDS and written out so that the records
-// of one digit form one contiguous run at the place reserved for them.
-//   rec[i], live[i]     the lane's records and whether each exists
-//   digit_of(cell)      digit of a record
-//   reserve(d, n, room) output index where this step's n records of digit d go;
-//                       sets `room` to how many of them still fit there
-//   pack(d, r)          the word to store for record r of digit d; bit 31 of the
-//                       result's `where` selects the output array
-//   copy(where, w)      stores word w at output index (where & 0x7fffffff)
-//   spill(r)            takes a record that found its group full
-// Records are packed and given their output index when they are staged, so
-// that writing them out is a copy.  Must be entered by the whole workgroup, with
+// One partition step of a workgroup: up to kPartTile record words held in
+// registers are grouped by digit (< kMaxCoarse) in LDS and written out so that
+// the records of one digit form one contiguous run at the place reserved for
+// them.
+//   word[i], live[i]    the lane's record words and whether each exists
+//   dig[i]              digit of each record (0 where there is none)
+//   out                 the output array
+//   reserve(d, n)       asks for room for this step's n records of digit d and
+//                       returns how many records of d asked before (one global
+//                       atomic); called by lane 64 + d
+//   room_of(d)          x = index in `out` where the room of digit d begins,
+//                       y = its size; called by lane 64 + d
+//   spill(d, w)         takes a record of digit d that found its group full
+// The phases: (1) every record gets its rank within its digit from the LDS
+// counters; (2) one wavefront scans the 256 counts, which gives every digit its
+// first staging slot, while lane 64 + d issues the reservation for digit d;
+// (3) the records are staged in digit order, each with its digit and rank -
+// the reservations are still in flight meanwhile, and their lanes store the
+// results when they arrive; (4) the stage is written out in order: a record's
+// output index is its digit's reserved index plus its rank, so that a wavefront
+// writes a few contiguous runs.  Must be entered by the whole workgroup, with
 // s.count[] zero; leaves s.count[] zero again.
 struct Staged {
     uint32_t word;
-    uint32_t where;
+    uint32_t digit_rank;         // digit << 16 | rank within the digit in this step
 };
-constexpr uint32_t kNowhere = 0xffffffffu;      // a staged slot whose record was spilled
+static_assert(kPartTile <= 65536, "a rank takes 16 bits of a staged record");
 
 struct PartitionLds {
     Staged stage[kPartTile];
-    uint32_t count[kMaxCoarse];
-    uint4 place[kMaxCoarse];     // per digit: x = first staging slot, y = first output index,
-                                 // z = records of this step that still fit there (one 128-bit read)
+    __attribute__((aligned(16))) uint32_t count[kMaxCoarse];
+    uint32_t first_slot[kMaxCoarse];   // per digit: first staging slot of this step's records
+    uint2 reserved[kMaxCoarse];        // per digit: x = output index of this step's first record,
+                                       // y = how many of this step's records still fit there
+    uint2 limit[kMaxCoarse];           // coarse level, per digit: x = first output index of its room, y = its room
     uint32_t total;
 };
 
-template <typename DigitOf, typename Reserve, typename Pack, typename Copy, typename Spill>
-__device__ __forceinline__ void partition_step(PartitionLds &s, const Record (&rec)[kPartItems],
-                                               const bool (&live)[kPartItems], DigitOf digit_of,
-                                               Reserve reserve, Pack pack, Copy copy, Spill spill)
+constexpr int kRankBatch = 4;     // records of a lane ranked together (their LDS atomics in flight at once)
+
+template <typename Reserve, typename RoomOf, typename Spill>
+__device__ __forceinline__ void partition_step(PartitionLds &s, uint32_t *__restrict__ out,
+                                               const uint32_t (&word)[kPartItems],
+                                               const bool (&live)[kPartItems],
+                                               const uint32_t (&dig)[kPartItems], Reserve reserve,
+                                               RoomOf room_of, Spill spill)
 {
-    static_assert(kMaxCoarse == 256 && kPartThreads >= 256, "one wavefront scans 4 digits per lane");
-    uint32_t dig[kPartItems], rank[kPartItems];
+    static_assert(kMaxCoarse == 256 && kPartThreads >= 64 + kMaxCoarse, "one wavefront scans 4 digits per lane");
+    uint32_t rank[kPartItems];
 #pragma unroll
-    for (int i = 0; i < kPartItems; ++i) {
-        dig[i] = live[i] ? digit_of(rec[i].cell) : 0u;
-        rank[i] = wave_rank(s.count, dig[i], live[i]);
+    for (int i0 = 0; i0 < kPartItems; i0 += kRankBatch) {
+        uint32_t b[kRankBatch], r[kRankBatch];
+        bool l[kRankBatch];
+#pragma unroll
+        for (int j = 0; j < kRankBatch; ++j) {
+            b[j] = dig[i0 + j];
+            l[j] = live[i0 + j];
+        }
+        wave_rank_all<kRankBatch>(s.count, b, l, r);
+#pragma unroll
+        for (int j = 0; j < kRankBatch; ++j) rank[i0 + j] = r[j];
     }
     __syncthreads();
     if (threadIdx.x < 64) {
-        // Exclusive scan of the 256 digit counts by one wavefront: 4 per lane,
-        // then a shuffle scan of the lane sums.
+        // Exclusive scan of the 256 digit counts by one wavefront: 4 per lane
+        // (one 128-bit read), then a scan of the lane sums.
         const uint32_t lane = threadIdx.x;
-        uint32_t c[4];
-        uint32_t sum = 0;
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            c[k] = s.count[4 * lane + k];
-            sum += c[k];
-        }
-        uint32_t incl = sum;
-        for (int off = 1; off < 64; off <<= 1) {
-            const uint32_t up = __shfl_up(incl, off, 64);
-            if (lane >= static_cast<uint32_t>(off)) incl += up;
-        }
-        uint32_t run = incl - sum;
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            s.place[4 * lane + k].x = run;
-            run += c[k];
-        }
+        const uint4 c = reinterpret_cast<const uint4 *>(s.count)[lane];
+        const uint32_t sum = c.x + c.y + c.z + c.w;
+        const uint32_t incl = wave_inclusive_sum(sum);
+        const uint32_t run = incl - sum;
+        reinterpret_cast<uint4 *>(s.first_slot)[lane] = make_uint4(run, run + c.x, run + c.x + c.y, run + c.x + c.y + c.z);
         if (lane == 63) s.total = incl;
     }
-    if (threadIdx.x >= 64 && threadIdx.x < 64 + kMaxCoarse) {
-        const uint32_t d = threadIdx.x - 64;
-        const uint32_t mine = s.count[d];
-        if (mine != 0) {
-            uint32_t fits = 0;
-            s.place[d].y = reserve(d, mine, fits);
-            s.place[d].z = fits;
-        }
+    const bool reserver = threadIdx.x >= 64 && threadIdx.x < 64 + kMaxCoarse;
+    const uint32_t my_digit = (threadIdx.x - 64) & (kMaxCoarse - 1);
+    uint32_t mine = 0, before = 0;
+    if (reserver) {
+        mine = s.count[my_digit];
+        if (mine != 0) before = reserve(my_digit, mine);       // not waited for yet
     }
     __syncthreads();
     if (threadIdx.x < kMaxCoarse) s.count[threadIdx.x] = 0;     // for the next step
+    uint32_t slot[kPartItems];
+#pragma unroll
+    for (int i = 0; i < kPartItems; ++i) slot[i] = s.first_slot[dig[i]];
 #pragma unroll
     for (int i = 0; i < kPartItems; ++i) {
-        if (live[i]) {
-            const uint32_t d = dig[i];
-            const uint4 place = s.place[d];
-            Staged e = pack(d, rec[i]);
-            e.where |= place.y + rank[i];
-            if (rank[i] >= place.z) {
-                e.where = kNowhere;
-                spill(rec[i]);
-            }
-            s.stage[place.x + rank[i]] = e;
-        }
+        if (live[i]) s.stage[slot[i] + rank[i]] = Staged{word[i], (dig[i] << 16) | rank[i]};
+    }
+    if (mine != 0) {
+        const uint2 room = room_of(my_digit);
+        s.reserved[my_digit] = make_uint2(room.x + before, before < room.y ? room.y - before : 0u);
     }
     __syncthreads();
+    // Write-out: every staged record of the lane is read before the first is
+    // stored.  (Slots from `total` on hold leftovers of earlier steps: read,
+    // since that is cheaper than a branch, and not used.)
     const uint32_t total = s.total;
-    for (uint32_t i = threadIdx.x; i < total; i += kPartThreads) {
-        const Staged e = s.stage[i];
-        if (e.where != kNowhere) copy(e.where, e.word);
+    Staged e[kPartItems];
+#pragma unroll
+    for (int u = 0; u < kPartItems; ++u) e[u] = s.stage[u * kPartThreads + threadIdx.x];
+    uint2 where[kPartItems];
+#pragma unroll
+    for (int u = 0; u < kPartItems; ++u) where[u] = s.reserved[(e[u].digit_rank >> 16) & (kMaxCoarse - 1)];
+#pragma unroll
+    for (int u = 0; u < kPartItems; ++u) {
+        if (u * kPartThreads + threadIdx.x < total) {
+            const uint32_t r = e[u].digit_rank & 0xffffu;
+            if (r < where[u].y) {
+                out[where[u].x + r] = e[u].word;
+            } else {
+                spill(e[u].digit_rank >> 16, e[u].word);
+            }
+        }
     }
 }
 
@@ -726,118 +775,108 @@ __device__ __forceinline__ void partition_step(PartitionLds &s, const Record (&r
 // workgroups take the steps (kPartTile triples of one buffer each) in turn and
 // keep the per-topic totals in LDS over all their steps.  Valid triples become
 // records: those of hot tiles go to their final place in plan.sorted, the others
-// to plan.tmp, grouped by coarse range.  A record whose group is full, and a
+// to plan.tmp, grouped by coarse range (one output index space: sorted lies
+// plan.sorted_base words after tmp).  A record whose group is full, and a
 // triple whose delta is too large for a record, is added to counts[] at once.
-// Dynamic LDS: [hot-tile table: 2 words per 32 tiles][T totals if LDS_TOTALS].
+// Dynamic LDS: [digit of every tile, one byte each, padded to a word][T totals
+// if LDS_TOTALS].
 //
 // Two workgroups share a CU (the grid is two per CU): while one waits for its
 // triples or for a barrier the other works.  That takes 8 wavefronts per SIMD,
-// i.e. at most 64 vector registers; the cap costs three spilled values and buys
-// 11 % of the kernel's time against one workgroup per CU.
+// i.e. at most 64 vector registers.
 template <bool LDS_TOTALS>
 __global__ __launch_bounds__(kPartThreads) __attribute__((amdgpu_waves_per_eu(8, 8)))
 void coarse_partition_kernel(const SparseArgs a, const BinPlan plan)
 {
     extern __shared__ uint32_t coarse_lds[];
     __shared__ PartitionLds s;
-    const uint32_t hot_words = (plan.n_tiles + 31) / 32;
-    // x = bitmap word, y = hot tiles before it: one 64-bit read per lookup
-    uint2 *hot = reinterpret_cast<uint2 *>(coarse_lds);
-    int32_t *lds_totals = reinterpret_cast<int32_t *>(coarse_lds + 2 * hot_words);
+    const uint32_t digit_words = (plan.n_tiles + 3) / 4;
+    const uint8_t *tile_digit = reinterpret_cast<const uint8_t *>(coarse_lds);
+    int32_t *lds_totals = reinterpret_cast<int32_t *>(coarse_lds + digit_words);
     const int T = a.T;
     const bool want_totals = a.totals != nullptr;
-    static_assert(kHotWords <= kPartThreads && kMaxCoarse <= kPartThreads, "one word per lane");
-    if (threadIdx.x < hot_words) {
-        hot[threadIdx.x] = make_uint2(plan.hot_bits[threadIdx.x], plan.hot_before[threadIdx.x]);
+    // (the table's allocation is padded to whole words)
+    for (uint32_t w = threadIdx.x; w < digit_words; w += kPartThreads) {
+        coarse_lds[w] = reinterpret_cast<const uint32_t *>(plan.tile_digit)[w];
     }
-    if (threadIdx.x < kMaxCoarse) s.count[threadIdx.x] = 0;
+    if (threadIdx.x < kMaxCoarse) {
+        s.count[threadIdx.x] = 0;
+        s.limit[threadIdx.x] = make_uint2(plan.digit_start[threadIdx.x], plan.digit_room[threadIdx.x]);
+    }
     if constexpr (LDS_TOTALS) {
         for (int t = threadIdx.x; t < T; t += kPartThreads) lds_totals[t] = 0;
     }
     __syncthreads();
 
     const uint32_t n_coarse = plan.n_coarse;
-    uint32_t *tmp = plan.tmp;
-    uint32_t *sorted = plan.sorted;
     int32_t *counts = a.counts;
     const uint32_t n_steps = a.step_start[a.n_buffers];
-    int n_bad = 0;
+    const uint32_t lane_offset = threadIdx.x * 12u;         // of the lane's first triple in a step
+    uint32_t n_bad = 0;                                     // of the wavefront (uniform)
     int k = 0;                                              // buffer of the current step (uniform)
 #pragma unroll 1
     for (uint32_t step = blockIdx.x; step < n_steps; step += gridDim.x) {
         while (step >= a.step_start[k + 1]) ++k;            // steps only grow; k < n_buffers
-        const int32_t *tr = a.triples[k];
-        const long long m = a.n_triples[k];
         const long long base = static_cast<long long>(step - a.step_start[k]) * kPartTile;
-        // All of the lane's triples are loaded before the first is used.
-        int word[kPartItems], topic[kPartItems], delta[kPartItems];
-        bool there[kPartItems], valid[kPartItems];
+        const long long left = a.n_triples[k] - base;       // >= 1
+        const uint32_t here = left < static_cast<long long>(kPartTile) ? static_cast<uint32_t>(left) : kPartTile;
+        const uint32_t last_offset = (here - 1) * 12u;
+        const char *from = reinterpret_cast<const char *>(a.triples[k] + 3 * base);     // uniform
+        // All of the lane's triples are loaded before the first is used.  (A
+        // lane past the end reloads the step's last triple: no branch around the
+        // load, so the loads of a lane issue back to back.)
+        int w[kPartItems], t[kPartItems], d[kPartItems];
+        bool in_range[kPartItems];
 #pragma unroll
         for (int i = 0; i < kPartItems; ++i) {
-            const long long r = base + i * kPartThreads + threadIdx.x;
-            there[i] = r < m;
-            // (a lane past the end reloads the buffer's last triple: no branch
-            // around the load, so the loads of a lane issue back to back)
-            valid[i] = load_triple(tr, there[i] ? r : m - 1, a.V, T, word[i], topic[i], delta[i]) && there[i];
+            const uint32_t offset = lane_offset + static_cast<uint32_t>(i) * kPartThreads * 12u;
+            in_range[i] = load_triple_at(from, min(offset, last_offset), a.V, T, w[i], t[i], d[i]);
         }
-        Record rec[kPartItems];
+        uint32_t word[kPartItems], dig[kPartItems];
         bool live[kPartItems];
 #pragma unroll
         for (int i = 0; i < kPartItems; ++i) {
-            if (there[i] && !valid[i]) ++n_bad;
-            rec[i].cell = static_cast<uint32_t>(word[i]) * static_cast<uint32_t>(T) + static_cast<uint32_t>(topic[i]);
-            rec[i].delta = delta[i];
-            const bool small = delta[i] >= -kSmallDeltaLimit && delta[i] < kSmallDeltaLimit;
-            live[i] = valid[i] && small && delta[i] != 0;
-            if (valid[i] && !small) add_relaxed(counts + rec[i].cell, delta[i]);
-            if (valid[i] && want_totals && delta[i] != 0) {
+            const bool there = lane_offset + static_cast<uint32_t>(i) * kPartThreads * 12u <= last_offset;
+            const bool valid = there && in_range[i];
+            n_bad += static_cast<uint32_t>(__popcll(__ballot(there && !in_range[i])));
+            const uint32_t cell = static_cast<uint32_t>(w[i]) * static_cast<uint32_t>(T) + static_cast<uint32_t>(t[i]);
+            const bool small = static_cast<uint32_t>(d[i] + kSmallDeltaLimit) < 2u * kSmallDeltaLimit;
+            live[i] = valid && small && d[i] != 0;
+            if (valid && !small) add_relaxed(counts + cell, d[i]);
+            if (valid && want_totals && d[i] != 0) {
                 if constexpr (LDS_TOTALS) {
-                    lds_add(&lds_totals[topic[i]], delta[i]);
+                    lds_add(&lds_totals[t[i]], d[i]);
                 } else {
-                    add_relaxed(a.totals + topic[i], delta[i]);
+                    add_relaxed(a.totals + t[i], d[i]);
                 }
             }
+            word[i] = pack_record(cell, d[i]);
+            dig[i] = live[i] ? tile_digit[cell >> kTileBits] : 0u;
         }
         partition_step(
-            s, rec, live,
-            [=](uint32_t cell) {
-                const uint32_t tile = cell >> kTileBits;
-                const uint2 entry = hot[tile >> 5];
-                const uint32_t bit = tile & 31;
-                const uint32_t hot_digit =
-                    n_coarse + entry.y + static_cast<uint32_t>(__popc(entry.x & ((1u << bit) - 1u)));
-                return ((entry.x >> bit) & 1u) != 0 ? hot_digit : tile >> kFineBits;
-            },
-            [=](uint32_t d, uint32_t n, uint32_t &fits) {
-                const uint32_t before = fetch_add_relaxed(plan.coarse_cursor + d * kCursorStride, n);
-                const uint32_t room = plan.digit_room[d];
-                fits = before < room ? room - before : 0u;
-                return plan.digit_start[d] + before;
-            },
-            [=](uint32_t d, Record r) {
-                return d < n_coarse ? Staged{pack_tmp(r), 0u} : Staged{pack_sorted(r), 0x80000000u};
-            },
-            [=](uint32_t where, uint32_t word) {
-                uint32_t *out = (where >> 31) != 0 ? sorted : tmp;
-                out[where & 0x7fffffffu] = word;
-            },
-            [=](Record r) { add_relaxed(counts + r.cell, r.delta); });
+            s, plan.tmp, word, live, dig,
+            [&](uint32_t dg, uint32_t n) { return fetch_add_relaxed(plan.coarse_cursor + dg * kCursorStride, n); },
+            [&](uint32_t dg) { return s.limit[dg]; },
+            [&](uint32_t dg, uint32_t v) {
+                // the record's coarse range: its digit, or that of its hot tile
+                const uint32_t range = dg < n_coarse ? dg : plan.hot_tile[dg - n_coarse] >> kFineBits;
+                add_relaxed(counts + ((range << kCoarseShift) | (v & kRangeMask)), record_delta(v));
+            });
         __syncthreads();                                    // the stage is reused by the next step
     }
 
     if constexpr (LDS_TOTALS) {
         __syncthreads();
         if (want_totals) {
-            for (int t = threadIdx.x; t < T; t += kPartThreads) {
-                const int32_t v = lds_totals[t];
-                if (v != 0) add_relaxed(a.totals + t, v);
+            for (int tt = threadIdx.x; tt < T; tt += kPartThreads) {
+                const int32_t v = lds_totals[tt];
+                if (v != 0) add_relaxed(a.totals + tt, v);
             }
         }
     }
-    if (a.rejected != nullptr) {
-        // Wavefront sum of the per-lane reject counts, one atomic per wavefront.
-        for (int off = 32; off > 0; off >>= 1) n_bad += __shfl_down(n_bad, off, 64);
-        if ((threadIdx.x & 63) == 0 && n_bad != 0) add_relaxed(a.rejected, n_bad);
+    // One atomic per wavefront for its rejected triples.
+    if (a.rejected != nullptr && (threadIdx.x & 63) == 0 && n_bad != 0) {
+        add_relaxed(a.rejected, static_cast<int32_t>(n_bad));
     }
 }
 
@@ -862,27 +901,25 @@ __global__ __launch_bounds__(kPartThreads) void fine_partition_kernel(int32_t *c
     const uint32_t begin = plan.tmp_start[c] + (g - plan.coarse_part_start[c]) * kPartTile;
     const uint32_t end = min(begin + kPartTile, plan.tmp_start[c] + in_range);
     if (begin >= end) return;                                 // uniform: room nobody needed
-    Record rec[kPartItems];
+    uint32_t word[kPartItems], dig[kPartItems];
     bool live[kPartItems];
 #pragma unroll
     for (int i = 0; i < kPartItems; ++i) {
         const uint32_t r = begin + i * kPartThreads + threadIdx.x;
         live[i] = r < end;
-        rec[i] = live[i] ? unpack_tmp(plan.tmp[r], c) : Record{0u, 0};
+        word[i] = plan.tmp[min(r, end - 1)];                  // (no branch around the load)
+        dig[i] = live[i] ? (word[i] >> kTileBits) & (kFinePerCoarse - 1) : 0u;
     }
-    uint32_t *sorted = plan.sorted;
     partition_step(
-        s, rec, live, [](uint32_t cell) { return (cell >> kTileBits) & (kFinePerCoarse - 1); },
-        [=](uint32_t f, uint32_t n, uint32_t &fits) {
-            const uint32_t tile = first_tile + f;
-            const uint32_t before = fetch_add_relaxed(plan.fine_cursor + tile * kCursorStride, n);
-            const uint32_t room = plan.tile_start[tile + 1] - plan.tile_start[tile];
-            fits = before < room ? room - before : 0u;
-            return plan.tile_start[tile] + before;
+        s, plan.sorted, word, live, dig,
+        [&](uint32_t f, uint32_t n) { return fetch_add_relaxed(plan.fine_cursor + (first_tile + f) * kCursorStride, n); },
+        [&](uint32_t f) {
+            const uint32_t at = plan.tile_start[first_tile + f];
+            return make_uint2(at, plan.tile_start[first_tile + f + 1] - at);
         },
-        [](uint32_t, Record r) { return Staged{pack_sorted(r), 0u}; },
-        [=](uint32_t where, uint32_t word) { sorted[where] = word; },
-        [=](Record r) { add_relaxed(counts + r.cell, r.delta); });
+        [&](uint32_t, uint32_t v) {
+            add_relaxed(counts + ((c << kCoarseShift) | (v & kRangeMask)), record_delta(v));
+        });
 }
 
 // Accumulate: workgroup g takes up to kAccChunk records of the room of one
@@ -903,7 +940,7 @@ __device__ __forceinline__ void accumulate_records(int32_t *image, const uint32_
     const uint32_t last = max(first, end / 4 * 4);
     auto add_one = [&](uint32_t r) {
         const uint32_t v = sorted[r];
-        lds_add(&image[v & (kTileCells - 1)], static_cast<int32_t>(v) >> kTileBits);
+        lds_add(&image[v & (kTileCells - 1)], record_delta(v));
     };
     if (threadIdx.x < first - begin) add_one(begin + threadIdx.x);
     if (threadIdx.x < end - last) add_one(last + threadIdx.x);
@@ -923,7 +960,7 @@ __device__ __forceinline__ void accumulate_records(int32_t *image, const uint32_
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const uint32_t v = x[u][j];
-                lds_add(&image[v & (kTileCells - 1)], static_cast<int32_t>(v) >> kTileBits);
+                lds_add(&image[v & (kTileCells - 1)], record_delta(v));
             }
         }
     }
@@ -1159,7 +1196,7 @@ size_t slots_for(long long n, uint32_t n_tiles, long long period)
     const double tiles = n_tiles;
     double bound = (least + kRoomSigmas * __builtin_sqrt(tiles * least) + kRoomFloor * tiles) * (n / least) + tiles;
     bound = bound * 1.001 + 1024.0;                      // rounding of the kernel's binary32 arithmetic
-    const double most = 2147483647.0 - 1.0;              // indices keep bit 31 free
+    const double most = 2147483647.0 - 256.0;            // sorted_base + n_slots stays below 2^32 - 1
     return static_cast<size_t>(bound < most ? bound : most);
 }
 
@@ -1192,9 +1229,10 @@ size_t plan_layout(int32_t V, int32_t T, long long n, char *ws, BinPlan *plan)
     char *tmp_start = take(sizeof(uint32_t) * (n_coarse + 1));
     char *digit_start = take(sizeof(uint32_t) * kMaxCoarse);
     char *digit_room = take(sizeof(uint32_t) * kMaxCoarse);
-    char *hot_bits = take(sizeof(uint32_t) * (kHotWords + 1));
-    char *hot_before = take(sizeof(uint32_t) * (kHotWords + 1));
+    char *tile_digit = take((static_cast<size_t>(n_tiles) + 3) / 4 * 4);     // whole words
+    const size_t tmp_at = off;
     char *tmp = take(sizeof(uint32_t) * n_slots);
+    const size_t sorted_at = off;
     char *sorted = take(sizeof(uint32_t) * n_slots);
     if (plan != nullptr) {
         plan->hist = reinterpret_cast<uint32_t *>(hist);
@@ -1208,10 +1246,10 @@ size_t plan_layout(int32_t V, int32_t T, long long n, char *ws, BinPlan *plan)
         plan->tmp_start = reinterpret_cast<uint32_t *>(tmp_start);
         plan->digit_start = reinterpret_cast<uint32_t *>(digit_start);
         plan->digit_room = reinterpret_cast<uint32_t *>(digit_room);
-        plan->hot_bits = reinterpret_cast<uint32_t *>(hot_bits);
-        plan->hot_before = reinterpret_cast<uint32_t *>(hot_before);
+        plan->tile_digit = reinterpret_cast<uint8_t *>(tile_digit);
         plan->tmp = reinterpret_cast<uint32_t *>(tmp);
         plan->sorted = reinterpret_cast<uint32_t *>(sorted);
+        plan->sorted_base = static_cast<uint32_t>((sorted_at - tmp_at) / sizeof(uint32_t));
         plan->n_tiles = n_tiles;
         plan->n_coarse = n_coarse;
         plan->n_slots = static_cast<uint32_t>(n_slots);
@@ -1327,7 +1365,7 @@ extern "C" mlf_status mlf_sparse_scatter_add(int32_t *counts, int32_t *totals, i
     if (!launch_kernel(plan_kernel, dim3(1), dim3(kPlanThreads), 0, s, plan)) return MLF_EHIP;
     const uint32_t n_steps = a.step_start[used];
     const unsigned coarse_grid = n_steps < kCoarseWorkgroups ? n_steps : kCoarseWorkgroups;
-    const size_t hot_lds = static_cast<size_t>((plan.n_tiles + 31) / 32) * 2 * sizeof(uint32_t);
+    const size_t hot_lds = static_cast<size_t>((plan.n_tiles + 3) / 4) * sizeof(uint32_t);   // digit of every tile
     const bool lds_totals = totals != nullptr && T <= kCoarseLdsTopics;
     const bool coarse_ok =
         lds_totals ? launch_kernel(coarse_partition_kernel<true>, dim3(coarse_grid), dim3(kPartThreads),
