@@ -432,7 +432,7 @@ __global__ __launch_bounds__(kThreads) void clear_kernel(uint32_t *p, uint32_t n
 }
 
 // Exclusive prefix sums of N values per lane over the kPlanThreads lanes of
-// the workgroup: shuffles inside each wavefront, then the wavefront totals
+// the workgroup: a scan inside each wavefront, then the wavefront totals
 // through LDS.  excl[k] = sum of v[k] over the lanes before this one, total[k] =
 // sum over all lanes.  Two barriers; `wave_sums` is reused by the next call.
 constexpr int kPlanWaves = kPlanThreads / 64;
@@ -444,14 +444,7 @@ __device__ __forceinline__ void block_scan(const uint32_t (&v)[N], uint32_t (&ex
     const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     uint32_t incl[N];
 #pragma unroll
-    for (int k = 0; k < N; ++k) incl[k] = v[k];
-    for (int off = 1; off < 64; off <<= 1) {
-#pragma unroll
-        for (int k = 0; k < N; ++k) {
-            const uint32_t up = __shfl_up(incl[k], off, 64);
-            if (lane >= static_cast<uint32_t>(off)) incl[k] += up;
-        }
-    }
+    for (int k = 0; k < N; ++k) incl[k] = wave_inclusive_sum(v[k]);
     if (lane == 63) {
 #pragma unroll
         for (int k = 0; k < N; ++k) wave_sums[k][wave] = incl[k];
@@ -489,69 +482,92 @@ __device__ __forceinline__ void block_scan(const uint32_t (&v)[N], uint32_t (&ex
 // than spare digits.  The digit of every tile (its coarse range, or n_coarse +
 // its rank among the hot tiles) is published as a table of one byte per tile.
 //
-// Lane i looks after the tiles i, i + kPlanThreads, ... (one per round); the
-// rooms are kept in LDS, and every table over the tiles is a running block scan
-// over the rounds.  (The rounds are loops, not unrolled: the kernel runs once
-// per call, and straight-line code would be fetched from memory once.)
+// Lane i looks after `per_lane` CONSECUTIVE tiles, so every table over the
+// tiles takes a serial pass inside each lane plus one block scan of the lane
+// sums; the per-tile rooms are kept in LDS between the passes and the sampled
+// counts are read again in each (they stay cached).
 constexpr int kHotShifts = 24;      // a hot tile holds at least total >> (kHotShifts - 1) sampled triples
+constexpr uint32_t kWantSplit = 20; // lane sums of rooms are scanned as two words of 20 and 12 bits
 
 __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const BinPlan plan)
 {
     static_assert(kMaxCoarse <= kPlanThreads, "the tables over coarse digits take one round");
+    static_assert(kMaxTiles / kPlanThreads <= 32, "a lane's hot tiles are one bit each of a word");
     __shared__ uint32_t wave_sums[3][kPlanWaves];
     __shared__ uint32_t tiles_at_least[kHotShifts];
     __shared__ uint32_t hot_in_range[kMaxCoarse];     // room of the hot tiles of each coarse range
+    __shared__ uint32_t range_start[kMaxCoarse + 1];  // tile_start at the first tile of each coarse range
+    __shared__ uint32_t hot_room[kMaxCoarse];         // room of each hot tile, by its rank
     __shared__ uint32_t s_threshold;
     __shared__ uint32_t room[kMaxTiles];              // room per tile
     const uint32_t n_tiles = plan.n_tiles;
     const uint32_t n_coarse = plan.n_coarse;
-    const uint32_t n_slots = plan.n_slots;
+    const uint32_t n_slots = plan.n_slots;            // < 2^31
     const uint32_t lane = threadIdx.x & 63;
+    const uint32_t per_lane = (n_tiles + kPlanThreads - 1) / kPlanThreads;
+    const uint32_t lo = min(threadIdx.x * per_lane, n_tiles);
+    const uint32_t hi = min(lo + per_lane, n_tiles);
 
     if (threadIdx.x < kHotShifts) tiles_at_least[threadIdx.x] = 0;
     if (threadIdx.x < kMaxCoarse) hot_in_range[threadIdx.x] = 0;
 
-    // tile_start: exclusive scan of the rooms, cut off at n_slots; and the
-    // size of the sample.
-    uint32_t placed = 0, sample = 0;
-#pragma unroll 1
-    for (uint32_t base = 0; base < n_tiles; base += kPlanThreads) {
-        const uint32_t b = base + threadIdx.x;
-        const uint32_t h = b < n_tiles ? plan.hist[b] : 0u;
+    // Pass 1: the room every tile asks for, each cut at n_slots; lane sums.
+    unsigned long long asked = 0;
+    uint32_t sampled = 0;
+#pragma unroll 4
+    for (uint32_t b = lo; b < hi; ++b) {
+        const uint32_t h = plan.hist[b];
         const float hf = static_cast<float>(h);
         const float want = (hf + kRoomSigmas * sqrtf(hf) + kRoomFloor) * plan.per_sampled + 1.0f;
-        // (want stays far below 2^32: h * per_sampled is about the tile's share of < 2^31 triples)
-        const uint32_t v[2] = {b < n_tiles ? static_cast<uint32_t>(fminf(want, 4.0e9f)) : 0u, h};
-        uint32_t e[2], t[2];
-        block_scan<2>(v, e, t, wave_sums);
-        // Saturating: once the running total has reached n_slots every later room is 0.
-        const unsigned long long lo = static_cast<unsigned long long>(placed) + e[0];
-        const unsigned long long hi = lo + v[0];
-        const uint32_t start = lo < n_slots ? static_cast<uint32_t>(lo) : n_slots;
-        const uint32_t stop = hi < n_slots ? static_cast<uint32_t>(hi) : n_slots;
-        if (b < n_tiles) {
-            plan.tile_start[b] = start;
-            room[b] = stop - start;
-        } else if (b < kMaxTiles) {
-            room[b] = 0;
-        }
-        const unsigned long long all = static_cast<unsigned long long>(placed) + t[0];
-        placed = all < n_slots ? static_cast<uint32_t>(all) : n_slots;
-        sample += t[1];
+        const uint32_t w = static_cast<uint32_t>(fminf(want, static_cast<float>(n_slots)));
+        room[b] = w;
+        asked += w;
+        sampled += h;
     }
-    if (threadIdx.x == 0) plan.tile_start[n_tiles] = placed;
+    uint32_t first;                                   // tile_start of the lane's first tile
+    uint32_t sample;
+    {
+        const uint32_t mine = asked < n_slots ? static_cast<uint32_t>(asked) : n_slots;
+        const uint32_t v[3] = {mine & ((1u << kWantSplit) - 1), mine >> kWantSplit, sampled};
+        uint32_t e[3], t[3];
+        block_scan<3>(v, e, t, wave_sums);
+        const unsigned long long before = (static_cast<unsigned long long>(e[1]) << kWantSplit) + e[0];
+        const unsigned long long all = (static_cast<unsigned long long>(t[1]) << kWantSplit) + t[0];
+        first = before < n_slots ? static_cast<uint32_t>(before) : n_slots;
+        sample = t[2];
+        if (threadIdx.x == 0) {
+            const uint32_t placed = all < n_slots ? static_cast<uint32_t>(all) : n_slots;
+            plan.tile_start[n_tiles] = placed;
+            range_start[n_coarse] = placed;
+        }
+    }
+    // tile_start: running sum inside the lane, saturating at n_slots (once the
+    // total has reached n_slots every later room is 0).
+    {
+        uint32_t at = first;
+        for (uint32_t b = lo; b < hi; ++b) {
+            const uint32_t stop = min(at + room[b], n_slots);       // both terms are at most n_slots < 2^31
+            plan.tile_start[b] = at;
+            room[b] = stop - at;
+            if ((b & (kFinePerCoarse - 1)) == 0) range_start[b >> kFineBits] = at;
+            at = stop;
+        }
+    }
 
-    // Threshold of the hot tiles (on the sampled counts).
-#pragma unroll 1
-    for (uint32_t base = 0; base < n_tiles; base += kPlanThreads) {
-        const uint32_t b = base + threadIdx.x;
-        const uint32_t mine = b < n_tiles ? plan.hist[b] : 0u;
-#pragma unroll 1
+    // Pass 2: threshold of the hot tiles (on the sampled counts).
+    {
+        uint32_t at_least[kHotShifts];
+#pragma unroll
+        for (int j = 0; j < kHotShifts; ++j) at_least[j] = 0;
+        for (uint32_t b = lo; b < hi; ++b) {
+            const uint32_t h = plan.hist[b];
+#pragma unroll
+            for (int j = 0; j < kHotShifts; ++j) at_least[j] += (h != 0 && h >= (sample >> j)) ? 1u : 0u;
+        }
+#pragma unroll
         for (int j = 0; j < kHotShifts; ++j) {
-            const unsigned long long heavy = __ballot(mine != 0 && mine >= (sample >> j));
-            if (lane == 0 && heavy != 0) {
-                lds_fetch_add(&tiles_at_least[j], static_cast<uint32_t>(__popcll(heavy)));
-            }
+            const uint32_t in_wave = wave_inclusive_sum(at_least[j]);
+            if (lane == 63 && in_wave != 0) lds_fetch_add(&tiles_at_least[j], in_wave);
         }
     }
     __syncthreads();
@@ -566,37 +582,44 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const BinPlan plan)
     __syncthreads();
     const uint32_t threshold = s_threshold;
 
-    // Hot tiles: digit of each (its rank among the hot tiles), hot room per
-    // coarse range, the digit of every tile; and the
-    // accumulate work items (kAccChunk records of room each) of the tiles that
-    // are not hot.
-    uint32_t n_hot = 0, n_items = 0;
-#pragma unroll 1
-    for (uint32_t base = 0; base < n_tiles; base += kPlanThreads) {
-        const uint32_t b = base + threadIdx.x;
-        const uint32_t sampled = b < n_tiles ? plan.hist[b] : 0u;
-        const uint32_t mine = room[b];
-        const bool hot = sampled != 0 && sampled >= threshold;
-        const uint32_t v[2] = {hot ? 1u : 0u, hot ? 0u : (mine + kAccChunk - 1) / kAccChunk};
+    // Pass 3: hot tiles (rank, room per coarse range), the digit of every tile,
+    // and the accumulate work items (kAccChunk records of room each) of the tiles
+    // that are not hot.
+    uint32_t n_hot = 0;
+    {
+        uint32_t hot_mask = 0, my_hot = 0, my_items = 0;
+        for (uint32_t b = lo; b < hi; ++b) {
+            const uint32_t h = plan.hist[b];
+            const bool hot = h != 0 && h >= threshold;
+            hot_mask |= (hot ? 1u : 0u) << (b - lo);
+            my_hot += hot ? 1u : 0u;
+            my_items += hot ? 0u : (room[b] + kAccChunk - 1) / kAccChunk;
+        }
+        const uint32_t v[2] = {my_hot, my_items};
         uint32_t e[2], t[2];
         block_scan<2>(v, e, t, wave_sums);
-        const uint32_t slot = n_hot + e[0];
-        if (hot) {
-            plan.hot_tile[slot] = b;
-            plan.digit_start[n_coarse + slot] = plan.sorted_base + plan.tile_start[b];      // this lane wrote it
-            plan.digit_room[n_coarse + slot] = mine;
-            lds_fetch_add(&hot_in_range[b >> kFineBits], mine);
-        }
-        if (b < n_tiles) {
-            plan.chunk_start[b] = n_items + e[1];
+        uint32_t slot = e[0], item = e[1], at = first;
+        for (uint32_t b = lo; b < hi; ++b) {
+            const bool hot = ((hot_mask >> (b - lo)) & 1u) != 0;
+            const uint32_t mine = room[b];
+            plan.chunk_start[b] = item;
             plan.tile_digit[b] = static_cast<uint8_t>(hot ? n_coarse + slot : b >> kFineBits);
+            if (hot) {
+                plan.hot_tile[slot] = b;
+                plan.digit_start[n_coarse + slot] = plan.sorted_base + at;
+                plan.digit_room[n_coarse + slot] = mine;
+                hot_room[slot] = mine;
+                lds_fetch_add(&hot_in_range[b >> kFineBits], mine);
+                ++slot;
+            } else {
+                item += (mine + kAccChunk - 1) / kAccChunk;
+            }
+            at += mine;
         }
-        n_hot += t[0];
-        n_items += t[1];
+        n_hot = t[0];
+        if (threadIdx.x == 0) plan.chunk_start[n_tiles] = t[1];
     }
-    if (threadIdx.x == 0) plan.chunk_start[n_tiles] = n_items;
     __syncthreads();
-    __threadfence_block();
 
     // Per coarse range: the room of its tiles that still go through the fine
     // level, and the fine partition steps (kPartTile records each) that room
@@ -605,13 +628,9 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const BinPlan plan)
     {
         const uint32_t c = threadIdx.x;
         uint32_t cold = 0;
-        if (c < n_coarse) {
-            const uint32_t lo = c << kFineBits;
-            const uint32_t hi = min(lo + kFinePerCoarse, n_tiles);
-            cold = plan.tile_start[hi] - plan.tile_start[lo] - hot_in_range[c];
-        }
+        if (c < n_coarse) cold = range_start[c + 1] - range_start[c] - hot_in_range[c];
         uint32_t hot_items = 0;
-        if (c < n_hot) hot_items = (room[plan.hot_tile[c]] + kAccChunk - 1) / kAccChunk;
+        if (c < n_hot) hot_items = (hot_room[c] + kAccChunk - 1) / kAccChunk;
         const uint32_t v[3] = {cold, (cold + kPartTile - 1) / kPartTile, hot_items};
         uint32_t e[3], t[3];
         block_scan<3>(v, e, t, wave_sums);
