@@ -71,6 +71,11 @@ def _load():
     lib.orc_sum_sq_f32.restype = c.c_double
     lib.orc_sum_sq_diff_f32.argtypes = [c.c_void_p, c.c_void_p, c.c_int64]
     lib.orc_sum_sq_diff_f32.restype = c.c_double
+    lib.orc_sum_sq_bf16.argtypes = [c.c_void_p, c.c_int64]
+    lib.orc_sum_sq_bf16.restype = c.c_double
+    lib.orc_divergence_bound.argtypes = [c.c_double, c.POINTER(c.c_double), f32p, i32p, c.c_int,
+                                         c.c_double, c.c_double]
+    lib.orc_divergence_bound.restype = c.c_double
     lib.orc_scatter_add.argtypes = [c.c_void_p, c.c_void_p, c.c_int32,
                                     c.c_int32, pp, c.POINTER(c.c_int64),
                                     c.c_int, c.c_int32, c.c_int32, c.c_int32,
@@ -248,15 +253,39 @@ def apply_grouped(model, momentum, updates, order, weights, group_len, lr, mu, t
 
 
 def sum_sq(x, threads=1):
-    """||x||_2^2 of a float32 vector: correctly rounded to binary64 with one
+    """||x||_2^2 of a float32 vector, or of a bfloat16 one given as uint16 bit
+    patterns (widened exactly first): correctly rounded to binary64 with one
     thread; with several, each slice's exact sum is rounded before the slices are
     combined (exactly), so the result is within a few units in the last place."""
     import math
     lib = _load()
+    if x.dtype == np.uint16:
+        assert x.flags["C_CONTIGUOUS"], "x must be contiguous"
+        jobs = [(lambda lo=lo, hi=hi: lib.orc_sum_sq_bf16(x.ctypes.data + 2 * lo, hi - lo))
+                for lo, hi in _slices(x.shape[0], threads)]
+        return math.fsum(_run(jobs, threads))
     _f32_inplace(x, "x", x.shape[0])
     jobs = [(lambda lo=lo, hi=hi: lib.orc_sum_sq_f32(x.ctypes.data + 4 * lo, hi - lo))
             for lo, hi in _slices(x.shape[0], threads)]
     return math.fsum(_run(jobs, threads))
+
+
+def divergence_bound(h_norm, g_norms, weights, group_len, lr, mu):
+    """Upper bound of ||w_after - w_before||_2 for a batch applied as
+    len(group_len) server steps, from ||h0|| and the norms ||g|| of the committed
+    updates in sequence (weights: one per committed update in sequence, or None)."""
+    lib = _load()
+    g = np.ascontiguousarray(g_norms, dtype=np.float64)
+    gl = np.ascontiguousarray(group_len, dtype=np.int32)
+    assert int(gl.sum()) == g.shape[0] and (gl >= 1).all(), "the groups must tile the sequence"
+    wt = None
+    if weights is not None:
+        wt = np.ascontiguousarray(weights, dtype=np.float32)
+        assert wt.shape[0] == g.shape[0]
+    return lib.orc_divergence_bound(
+        float(h_norm), g.ctypes.data_as(ctypes.POINTER(ctypes.c_double)),
+        wt.ctypes.data_as(ctypes.POINTER(ctypes.c_float)) if wt is not None else None,
+        gl.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)), int(gl.shape[0]), float(lr), float(mu))
 
 
 def sum_sq_diff(a, b, threads=1):

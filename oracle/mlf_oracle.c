@@ -40,6 +40,8 @@
  *  - orc_sum_sq_*          Table 1 (push carries update_norm) and Sec. 5.3
  *                          (divergence bound from ||h||, ||u_i||; exact
  *                          divergence ||w_s - w_r||): squared 2-norms.
+ *  - orc_divergence_bound  Sec. 5.3: the upper bound of a batch's divergence
+ *                          that the scheduler forms from those norms.
  *  - orc_counts_add_dense  Sec. 6: the same LDA update exchanged as dense V x T
  *                          delta matrices, summed over the workers.
  *  - orc_scatter_add       Sec. 6 "Datasets and ML models": an LDA worker's
@@ -49,6 +51,7 @@
  *                          per-topic totals.
  */
 #include <stddef.h>
+#include <math.h>
 #include <stdint.h>
 #include <string.h>
 
@@ -314,6 +317,63 @@ double orc_sum_sq_diff_f32(const float *a, const float *b, int64_t n)
         acc += d * d;
     }
     return (double)acc;
+}
+
+/* The same for an update that arrives in bfloat16: every element is widened   */
+/* exactly, as the aggregation does, before it is squared.                     */
+double orc_sum_sq_bf16(const uint16_t *x, int64_t n)
+{
+    __float128 acc = 0;
+    for (int64_t i = 0; i < n; ++i) {
+        __float128 v = widen_bf16(x[i]);
+        acc += v * v;
+    }
+    return (double)acc;
+}
+
+/* ------------------------------------------------------------------------ */
+/* Upper bound of the divergence a batch causes (Sec. 5.3: the scheduler does   */
+/* not compute ||w_after - w_before||_2, it bounds it from the norms of the     */
+/* history and of the updates).  The batch is n_groups server steps of Eq. 2;   */
+/* step j applies u_j = -lr * (sum over the group's updates of wt * g).         */
+/* Unrolling Eq. 2 over the steps (the two-step case is printed in Sec. 3.3:    */
+/* (mu + mu^2) h0 + (1 + mu) u_1 + u_2):                                        */
+/*   w_after - w_before = (mu + ... + mu^S) h0                                  */
+/*                        + sum_j (1 + mu + ... + mu^(S-j)) u_j ,  j = 1..S     */
+/* and by the triangle inequality, for the norm of the whole and of each u_j,   */
+/*   bound = (mu + ... + mu^S) ||h0|| + sum_j (1 + ... + mu^(S-j)) ||u_j||,     */
+/*   ||u_j|| <= lr * sum over the group of |wt| * ||g||.                        */
+/* Its square is the printed form a1 ||h0||^2 + a2 ||u1||^2 + ... with every    */
+/* cross term taken at its Cauchy-Schwarz maximum.  g_norm[t] and wt[t] belong  */
+/* to the t-th committed update (wt NULL = 1); the groups tile the sequence.    */
+/* ------------------------------------------------------------------------ */
+double orc_divergence_bound(double h_norm, const double *g_norm, const float *wt,
+                            const int32_t *group_len, int n_groups, double lr, double mu)
+{
+    double bound = 0.0;
+    double geometric = 0.0;                 /* mu + mu^2 + ... + mu^S */
+    double power = 1.0;
+    for (int j = 0; j < n_groups; ++j) {
+        power *= mu;
+        geometric += power;
+    }
+    bound += fabs(geometric) * h_norm;
+    int t = 0;
+    for (int j = 0; j < n_groups; ++j) {
+        double u_norm = 0.0;                /* bound of ||u_j|| */
+        for (int i = 0; i < group_len[j]; ++i, ++t) {
+            u_norm += fabs(wt != 0 ? (double)wt[t] : 1.0) * g_norm[t];
+        }
+        u_norm *= fabs(lr);
+        double coefficient = 0.0;           /* 1 + mu + ... + mu^(S-1-j) */
+        double p = 1.0;
+        for (int i = j; i < n_groups; ++i) {
+            coefficient += p;
+            p *= mu;
+        }
+        bound += fabs(coefficient) * u_norm;
+    }
+    return bound;
 }
 
 /* ------------------------------------------------------------------------ */

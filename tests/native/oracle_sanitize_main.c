@@ -32,6 +32,9 @@ void orc_apply_grouped_bf16(float *model, float *momentum, const uint16_t *const
                             const int32_t *group_len, int n_groups, float lr, float mu);
 double orc_sum_sq_f32(const float *x, int64_t n);
 double orc_sum_sq_diff_f32(const float *a, const float *b, int64_t n);
+double orc_sum_sq_bf16(const uint16_t *x, int64_t n);
+double orc_divergence_bound(double h_norm, const double *g_norm, const float *wt, const int32_t *group_len,
+                            int n_groups, double lr, double mu);
 int64_t orc_scatter_add(int32_t *counts, int32_t *totals, int32_t V, int32_t T,
                         const int32_t *const *triples, const int64_t *n_triples, int K,
                         int32_t word_lo, int32_t word_hi, int32_t topic_lo, int32_t topic_hi,
@@ -92,8 +95,14 @@ static void dense_calls(int K, int64_t n, int M)
     orc_aggregate_apply_bf16(w, h, out, cub, K, n, order, M, weights, 0.1f, 0.9f);
     orc_apply_grouped_f32(w, h, cuf, K, n, order, M, weights, lens, n_groups, 0.1f, 0.9f);
     orc_apply_grouped_bf16(w, NULL, cub, K, n, order, M, NULL, lens, n_groups, 0.1f, 0.9f);
-    volatile double sink = orc_sum_sq_f32(w, n) + orc_sum_sq_diff_f32(w, h, n);
+    volatile double sink = orc_sum_sq_f32(w, n) + orc_sum_sq_diff_f32(w, h, n) + orc_sum_sq_bf16(ub[0], n);
+    double *g_norm = exact(sizeof(double) * (size_t)(M > 0 ? M : 1));
+    for (int t = 0; t < M; ++t) g_norm[t] = 1.0 + t;
+    /* (the weights of this driver are indexed by worker; any M of them will do here) */
+    sink += orc_divergence_bound(2.0, g_norm, weights, lens, n_groups, 0.1, 0.9);
+    sink += orc_divergence_bound(2.0, g_norm, NULL, lens, n_groups, 0.1, 0.9);
     (void)sink;
+    free(g_norm);
     for (int k = 0; k < K; ++k) {
         free(uf[k]);
         free(ub[k]);
