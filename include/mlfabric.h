@@ -200,6 +200,81 @@ mlf_status mlf_apply_grouped_norms(float *model, float *momentum,
                                    mlf_stream stream);
 
 /*
+ * The same two calls with the squared norm of every committed update as well
+ * (Table 1: a push carries update_norm; Sec. 5.3: the scheduler bounds the
+ * divergence from ||h|| and the ||u_i||).  The server or aggregator reads every
+ * update anyway, so the norms cost no further HBM traffic:
+ *
+ *   update_norm_sq[t] = sum_i U_order[t][i]^2,   t = 0 .. n_order - 1
+ *
+ * of the update as it arrived (before its weight; bfloat16 widened exactly), in
+ * the commit sequence.  norm_sq / norms_sq are as in the calls above.  Sums in
+ * binary64 in a fixed order (exact squares, rounded additions): repeatable bit
+ * for bit for the same arguments on the same device; the order depends on what
+ * the calls above list and on the number of compute units of the device, and a
+ * sum agrees with the exactly rounded one to about 1e-14 relative.  These
+ * variants keep one running sum per update and lane on chip and walk the
+ * vector with a fixed number of workgroups, which makes the pass itself a few
+ * per cent slower than mlf_aggregate_norm / mlf_apply_grouped_norms.
+ *
+ *   update_norm_sq  device, n_order doubles, 8-byte aligned; written
+ *   workspace       device scratch of mlf_update_norms_workspace_bytes(n) bytes
+ *                   (about 6.5 MiB whatever n), 16-byte aligned
+ */
+size_t mlf_update_norms_workspace_bytes(int64_t n);
+
+mlf_status mlf_aggregate_update_norms(const void *const *update_ptrs, int K, int64_t n,
+                                      mlf_dtype dtype, const int32_t *order, int n_order,
+                                      const float *weights, float *out, double *norm_sq,
+                                      double *update_norm_sq, void *workspace,
+                                      size_t workspace_bytes, mlf_stream stream);
+
+mlf_status mlf_apply_grouped_update_norms(float *model, float *momentum,
+                                          const void *const *update_ptrs, int K, int64_t n,
+                                          mlf_dtype dtype, const int32_t *order, int n_order,
+                                          const float *weights, const int32_t *group_len,
+                                          int n_groups, float lr, float mu, double *norms_sq,
+                                          double *update_norm_sq, void *workspace,
+                                          size_t workspace_bytes, mlf_stream stream);
+
+/*
+ * The scheduler's upper bound of the divergence a batch will cause (Sec. 5.3:
+ * ||w_s - w_r||_2 is approximated from above with the norms of the history and
+ * of the updates, and a schedule is admissible if the bound stays below
+ * Div_max).  For a batch applied as n_groups server steps of Eq. 2 (the shape
+ * mlf_apply_grouped takes; single updates are groups of length 1), unrolling
+ * Eq. 2 gives
+ *
+ *   w_after - w_before = (mu + ... + mu^S) h0 + sum_j (1 + mu + ... + mu^(S-j)) u_j
+ *   u_j = -lr * sum over group j of weights * g            (S = n_groups, j = 1..S)
+ *
+ * (the two-update case printed in Sec. 3.3 is (mu + mu^2) h0 + (1 + mu) u_1 + u_2)
+ * and the triangle inequality on the whole and on every u_j gives
+ *
+ *   bound = |mu + ... + mu^S| ||h0|| + |lr| sum_j |1 + ... + mu^(S-j)| sum_group |weight| ||g||.
+ *
+ * Its square is the paper's a1 ||h0||^2 + a2 ||u1||^2 + ... with every cross term
+ * at its Cauchy-Schwarz maximum (the printed list of cross terms names one
+ * product twice and omits another, and gives no constants).  The exact value,
+ * for comparison, is what mlf_apply_grouped_norms returns in norms_sq[1].
+ * Host arithmetic only, no GPU work; all pointers are host pointers.
+ *
+ *   h_norm_sq       ||h0||^2 of the history before the batch (0 without momentum)
+ *   update_norm_sq  n_order squared norms in the commit sequence, as
+ *                   mlf_*_update_norms return them
+ *   order, weights  as in mlf_apply_grouped (weights indexed by worker, NULL = 1)
+ *   bound           one double; written: an upper bound of ||w_after - w_before||_2
+ *
+ * MLF_EINVAL: NULL bound, K < 1, n_order outside [0, K], an index outside
+ * [0, K), groups that do not tile the sequence, a negative or NaN norm.
+ * MLF_EUNSUPPORTED: K > MLF_MAX_K.
+ */
+mlf_status mlf_divergence_bound(double h_norm_sq, const double *update_norm_sq,
+                                const int32_t *order, int n_order, int K,
+                                const float *weights, const int32_t *group_len,
+                                int n_groups, float lr, float mu, double *bound);
+
+/*
  * Exact server-replica divergence (Sec. 3.3 "Enforcing bounded consistency" and
  * Sec. 5.3: the replica is kept within ||w_s - w_r||_2 <= Div_max of the server).
  *   dist_sq[0] = sum_i (w_server[i] - w_replica[i])^2

@@ -12,12 +12,16 @@ from .binding import (  # noqa: F401
     mlf_aggregate,
     mlf_aggregate_apply,
     mlf_aggregate_norm,
+    mlf_aggregate_update_norms,
     mlf_apply_grouped,
     mlf_apply_grouped_norms,
+    mlf_apply_grouped_update_norms,
     mlf_counts_add_dense,
     mlf_divergence,
+    mlf_divergence_bound,
     mlf_divergence_static,
     mlf_norms_workspace_bytes,
+    mlf_update_norms_workspace_bytes,
     mlf_apply_ordered,
     mlf_sparse_scatter_add,
     mlf_sparse_workspace_bytes,

@@ -69,6 +69,22 @@ def raw():
                                             _c.c_float, _c.c_float, _c.c_void_p, _c.c_void_p,
                                             _c.c_size_t, _c.c_void_p]
     lib.mlf_apply_grouped_norms.restype = _c.c_int
+    lib.mlf_update_norms_workspace_bytes.argtypes = [_c.c_int64]
+    lib.mlf_update_norms_workspace_bytes.restype = _c.c_size_t
+    lib.mlf_aggregate_update_norms.argtypes = [vpp, _c.c_int, _c.c_int64, _c.c_int, i32p, _c.c_int,
+                                               f32p, _c.c_void_p, _c.c_void_p, _c.c_void_p,
+                                               _c.c_void_p, _c.c_size_t, _c.c_void_p]
+    lib.mlf_aggregate_update_norms.restype = _c.c_int
+    lib.mlf_apply_grouped_update_norms.argtypes = [_c.c_void_p, _c.c_void_p, vpp, _c.c_int,
+                                                   _c.c_int64, _c.c_int, i32p, _c.c_int, f32p,
+                                                   i32p, _c.c_int, _c.c_float, _c.c_float,
+                                                   _c.c_void_p, _c.c_void_p, _c.c_void_p,
+                                                   _c.c_size_t, _c.c_void_p]
+    lib.mlf_apply_grouped_update_norms.restype = _c.c_int
+    lib.mlf_divergence_bound.argtypes = [_c.c_double, _c.POINTER(_c.c_double), i32p, _c.c_int,
+                                         _c.c_int, f32p, i32p, _c.c_int, _c.c_float, _c.c_float,
+                                         _c.POINTER(_c.c_double)]
+    lib.mlf_divergence_bound.restype = _c.c_int
     lib.mlf_divergence.argtypes = [_c.c_void_p, _c.c_void_p, _c.c_int64, _c.c_void_p,
                                    _c.c_void_p, _c.c_size_t, _c.c_void_p]
     lib.mlf_divergence.restype = _c.c_int
@@ -240,6 +256,74 @@ def mlf_apply_grouped_norms(model, momentum, updates, order, weights, group_len,
                                        wp, gp, len(g), float(lr), float(mu), _ptr(norms_sq),
                                        _ptr(workspace), _nbytes(workspace), _stream(stream))
     return _done(st, check)
+
+
+def mlf_update_norms_workspace_bytes(n) -> int:
+    return int(raw().mlf_update_norms_workspace_bytes(int(n)))
+
+
+def _update_norms_out(t, n_order):
+    if t.dtype != torch.float64 or t.numel() < n_order:
+        raise ValueError("update_norm_sq must be a float64 device tensor of len(order) elements")
+
+
+def mlf_aggregate_update_norms(updates, order, weights, out, norm_sq, update_norm_sq, workspace,
+                               n=None, stream=None, check=True):
+    """mlf_aggregate_norm, plus update_norm_sq[t] = sum of updates[order[t]]^2."""
+    n = out.numel() if n is None else int(n)
+    _state(out, n, "out")
+    if norm_sq.dtype != torch.float64 or norm_sq.numel() < 1:
+        raise ValueError("norm_sq must be a float64 device tensor")
+    tab, K, kind, o, op, w, wp = _dense_tables(updates, order, weights, n)
+    _update_norms_out(update_norm_sq, len(o))
+    st = raw().mlf_aggregate_update_norms(tab, K, n, kind, op, len(o), wp, _ptr(out), _ptr(norm_sq),
+                                          _ptr(update_norm_sq), _ptr(workspace), _nbytes(workspace),
+                                          _stream(stream))
+    return _done(st, check)
+
+
+def mlf_apply_grouped_update_norms(model, momentum, updates, order, weights, group_len, lr, mu,
+                                   norms_sq, update_norm_sq, workspace, n=None, stream=None,
+                                   check=True):
+    """mlf_apply_grouped_norms, plus update_norm_sq[t] = sum of updates[order[t]]^2."""
+    n = model.numel() if n is None else int(n)
+    _state(model, n, "model")
+    _state(momentum, n, "momentum")
+    if norms_sq.dtype != torch.float64 or norms_sq.numel() < 2:
+        raise ValueError("norms_sq must be a float64 device tensor of 2 elements")
+    tab, K, kind, o, op, w, wp = _dense_tables(updates, order, weights, n)
+    _update_norms_out(update_norm_sq, len(o))
+    g = np.ascontiguousarray(np.asarray(group_len, dtype=np.int32).reshape(-1))
+    gp = g.ctypes.data_as(_c.POINTER(_c.c_int32))
+    st = raw().mlf_apply_grouped_update_norms(_ptr(model), _ptr(momentum), tab, K, n, kind, op,
+                                              len(o), wp, gp, len(g), float(lr), float(mu),
+                                              _ptr(norms_sq), _ptr(update_norm_sq), _ptr(workspace),
+                                              _nbytes(workspace), _stream(stream))
+    return _done(st, check)
+
+
+def mlf_divergence_bound(h_norm_sq, update_norm_sq, order, K, weights, group_len, lr, mu,
+                         check=True):
+    """Upper bound of ||w_after - w_before||_2 for a batch (host arithmetic).  The
+    norms are host values: update_norm_sq[t] belongs to updates[order[t]]."""
+    u = np.ascontiguousarray(np.asarray(update_norm_sq, dtype=np.float64).reshape(-1))
+    o = np.ascontiguousarray(np.asarray(order, dtype=np.int32).reshape(-1))
+    g = np.ascontiguousarray(np.asarray(group_len, dtype=np.int32).reshape(-1))
+    w = wp = None
+    if weights is not None:
+        w = np.ascontiguousarray(np.asarray(weights, dtype=np.float32).reshape(-1))
+        if w.shape[0] != K:
+            raise ValueError("weights must have one entry per worker")
+        wp = w.ctypes.data_as(_c.POINTER(_c.c_float))
+    if u.shape[0] != o.shape[0]:
+        raise ValueError("one norm per committed update")
+    out = _c.c_double(0.0)
+    st = raw().mlf_divergence_bound(float(h_norm_sq), u.ctypes.data_as(_c.POINTER(_c.c_double)),
+                                    o.ctypes.data_as(_c.POINTER(_c.c_int32)), len(o), int(K), wp,
+                                    g.ctypes.data_as(_c.POINTER(_c.c_int32)), len(g), float(lr),
+                                    float(mu), _c.byref(out))
+    _done(st, check)
+    return out.value if st == MLF_OK else None
 
 
 def mlf_divergence(w_server, w_replica, dist_sq, workspace, n=None, stream=None, check=True):

@@ -35,6 +35,9 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 static_assert(MLF_MAX_K <= 64, "group boundaries are one bit per sequence position");
 
 enum Op { kAggregate = 0, kAggregateApply = 1, kApplyOrdered = 2, kApplyGrouped = 3 };
+// Which squared norms a kernel reduces besides its pass: none; those of the call
+// (one pair per workgroup); or those and one per committed update.
+enum Norms { kNoNorms = 0, kCallNorms = 1, kUpdateNorms = 2 };
 
 // Model + momentum up to this size are left to the caches between calls.
 constexpr long long kInfinityCacheBytes = 256ll << 20;
@@ -42,6 +45,12 @@ constexpr long long kInfinityCacheBytes = 256ll << 20;
 constexpr long long kMaxScalarGroups = 4096;
 // Elements in the smallest tile of any launch shape (64 lanes x 1 group x 4).
 constexpr long long kMinTileElements = 256;
+// Update-norm variants: doubles in a workgroup's row of partial sums (the two
+// sums of the call, then one per committed update), and the most workgroups
+// that ever walk the 128-bit region (wavefronts resident on the device: a few
+// per SIMD; the scratch is sized for this many rows plus the element-wise ones).
+constexpr size_t kUpdateNormRow = 2 + MLF_MAX_K;
+constexpr long long kUpdateNormMaxGroups = 8192;
 
 // Kernel argument block.  The host has already applied the scheduler's order:
 // u[t] / wt[t] belong to the t-th committed update (wt = 1 without weights:
@@ -56,7 +65,9 @@ struct DenseArgs {
     double *partials;       // norms variants: two partial sums per workgroup
     long long n;            // elements
     long long n_vec;        // leading elements on the 128-bit path (0 if unaligned)
-    unsigned tiles_vec;     // workgroups [0, tiles_vec) each own one 128-bit tile
+    unsigned tiles_vec;     // tiles of the 128-bit region
+    unsigned groups_vec;    // workgroups [0, groups_vec) take those tiles: one each (groups_vec ==
+                            // tiles_vec), or in turn with stride groups_vec (update-norm variants)
     unsigned xcds;          // XCDs of the device (workgroups go to them in turn)
     int M;                  // committed updates
     float lr;
@@ -123,28 +134,24 @@ struct BF16V4 {
 //    and the uncapped occupancy are kept (6.4 TB/s; the narrow capped shape
 //    drops to 3.4 TB/s);
 //  - state that stays cached between calls: wider tiles, no cap.
-template <typename IN, bool STREAMED, bool NORMS>
+template <typename IN, bool STREAMED, int NORMS>
 struct Shape;
 
-template <bool NORMS>
+template <int NORMS>
 struct Shape<F32, true, NORMS> {     // streamed state, binary32 updates
     static constexpr int kThreads = 64, kVpt = 1, kHalf = 8, kWaves = 1;
 };
-template <bool NORMS>
+template <int NORMS>
 struct Shape<BF16V4, true, NORMS> {  // streamed state, bfloat16 updates
     static constexpr int kThreads = 64, kVpt = 2, kHalf = 4, kWaves = 0;
 };
-template <bool NORMS>
+template <int NORMS>
 struct Shape<F32, false, NORMS> {    // cached state, binary32 updates
     static constexpr int kThreads = 64, kVpt = 2, kHalf = 8, kWaves = 0;
 };
-template <>
-struct Shape<BF16V8, false, false> { // cached state, bfloat16 updates
-    static constexpr int kThreads = 256, kVpt = 1, kHalf = 4, kWaves = 0;
-};
-template <>
-struct Shape<BF16V8, false, true> {  // the same with norms: one wavefront per workgroup
-    static constexpr int kThreads = 64, kVpt = 2, kHalf = 4, kWaves = 0;
+template <int NORMS>
+struct Shape<BF16V8, false, NORMS> { // cached state, bfloat16 updates; with norms one wavefront per workgroup
+    static constexpr int kThreads = NORMS != 0 ? 64 : 256, kVpt = NORMS != 0 ? 2 : 1, kHalf = 4, kWaves = 0;
 };
 
 __device__ __forceinline__ float from_bits(uint32_t b) { return __uint_as_float(b); }
@@ -247,7 +254,7 @@ __device__ __forceinline__ void server_step(float &w, float &h, float g, float l
 //   e0       first element of the region the groups are counted in
 //   g0       this lane's first group in that region
 //   n_groups groups in the region
-template <typename IN, int W, int OP, bool HAS_H, int STREAM, bool NORMS, int THREADS, int VPT,
+template <typename IN, int W, int OP, bool HAS_H, int STREAM, int NORMS, int THREADS, int VPT,
           int HALF, bool FULL>
 struct Tile {
     const DenseArgs &a;
@@ -259,10 +266,11 @@ struct Tile {
     float w[VPT][W];        // model         (apply variants)
     float h[VPT][W];        // history       (apply variants with momentum)
     float w_old[VPT][W];    // model before the call (norms variants)
+    double *update_sums;    // kUpdateNorms: LDS, [position][lane] running sum of squares of each update
 
     __device__ __forceinline__ Tile(const DenseArgs &args, long long e0, long long g0,
-                                    long long n_groups)
-        : a(args)
+                                    long long n_groups, double *lds_update_sums = nullptr)
+        : a(args), update_sums(lds_update_sums)
     {
 #pragma unroll
         for (int v = 0; v < VPT; ++v) {
@@ -305,6 +313,20 @@ struct Tile {
             const int t = t0 + c;
             const bool closes = OP == kApplyGrouped && ((a.group_end >> t) & 1ull) != 0;
             const bool opens = OP == kApplyGrouped && (t == 0 || ((a.group_end >> (t - 1)) & 1ull) != 0);
+            if constexpr (NORMS == kUpdateNorms) {
+                // The update as it arrived (before its weight); a binary32 square
+                // is exact in binary64.  Lanes without an element hold zeros.
+                double sq = 0.0;
+#pragma unroll
+                for (int v = 0; v < VPT; ++v) {
+#pragma unroll
+                    for (int j = 0; j < W; ++j) {
+                        const double xx = x[c][v][j];
+                        sq += xx * xx;
+                    }
+                }
+                update_sums[t * THREADS + threadIdx.x] += sq;       // the lane's own slot
+            }
 #pragma unroll
             for (int v = 0; v < VPT; ++v) {
 #pragma unroll
@@ -361,7 +383,7 @@ struct Tile {
                     if constexpr (HAS_H) load_state<W, STREAM>(h[v], a.momentum, e[v]);
                 }
             }
-            if constexpr (NORMS) {
+            if constexpr (NORMS != kNoNorms) {
 #pragma unroll
                 for (int j = 0; j < W; ++j) w_old[v][j] = w[v][j];
             }
@@ -411,7 +433,7 @@ struct Tile {
                 store_state<W, STREAM>(a.model, e[v], w[v]);
                 if constexpr (HAS_H) store_state<W, STREAM>(a.momentum, e[v], h[v]);
             }
-            if constexpr (NORMS) {
+            if constexpr (NORMS != kNoNorms) {
 #pragma unroll
                 for (int j = 0; j < W; ++j) {
                     if constexpr (OP == kAggregate) {
@@ -456,53 +478,76 @@ __device__ __forceinline__ long long xcd_tile(unsigned block, unsigned tiles, un
 // [n_vec, n): the ragged tail, or everything when a pointer of the call is not
 // 16-byte aligned.  Norms variants (one wavefront per workgroup) end with a
 // shuffle reduction in a fixed order and one pair of partial sums per workgroup.
-template <typename IN, int OP, bool HAS_H, int STREAM, bool NORMS, int THREADS, int VPT, int HALF,
+template <typename IN, int OP, bool HAS_H, int STREAM, int NORMS, int THREADS, int VPT, int HALF,
           int WAVES>
 __device__ __forceinline__ void dense_body(const DenseArgs &a)
 {
-    static_assert(!NORMS || THREADS == 64, "norms are reduced within one wavefront");
+    static_assert(NORMS == kNoNorms || THREADS == 64, "norms are reduced within one wavefront");
     constexpr int WV = IN::kVec;
     constexpr long long kTile = static_cast<long long>(THREADS) * VPT;
     double sums[2] = {0.0, 0.0};
-    if (blockIdx.x < a.tiles_vec) {
+    // kUpdateNorms: one running sum per committed update and lane, in dynamic LDS.
+    extern __shared__ double lds_update_sums[];
+    double *update_sums = nullptr;
+    if constexpr (NORMS == kUpdateNorms) {
+        update_sums = lds_update_sums;
+        for (int t = 0; t < a.M; ++t) update_sums[t * THREADS + threadIdx.x] = 0.0;
+    }
+    if (blockIdx.x < a.groups_vec) {
         const long long groups = a.n_vec / WV;
-        constexpr unsigned kRun = (STREAM == 0 && OP != kAggregate) ? kXcdRun : 0;
-        const long long base = xcd_tile<kRun>(blockIdx.x, a.tiles_vec, a.xcds) * kTile;
-        if (base + kTile <= groups) {
-            Tile<IN, WV, OP, HAS_H, STREAM, NORMS, THREADS, VPT, HALF, true>(a, 0, base + threadIdx.x, groups).run(sums);
-        } else {
-            Tile<IN, WV, OP, HAS_H, STREAM, NORMS, THREADS, VPT, HALF, false>(a, 0, base + threadIdx.x, groups).run(sums);
+        constexpr unsigned kRun = (STREAM == 0 && OP != kAggregate && NORMS != kUpdateNorms) ? kXcdRun : 0;
+        // (one tile per workgroup, except for the update-norm variants, whose
+        // workgroups take the tiles in turn and keep their sums over all of them)
+        for (unsigned tile = blockIdx.x; tile < a.tiles_vec; tile += a.groups_vec) {
+            const long long base = xcd_tile<kRun>(tile, a.tiles_vec, a.xcds) * kTile;
+            if (base + kTile <= groups) {
+                Tile<IN, WV, OP, HAS_H, STREAM, NORMS, THREADS, VPT, HALF, true>(a, 0, base + threadIdx.x, groups, update_sums).run(sums);
+            } else {
+                Tile<IN, WV, OP, HAS_H, STREAM, NORMS, THREADS, VPT, HALF, false>(a, 0, base + threadIdx.x, groups, update_sums).run(sums);
+            }
+            if constexpr (NORMS != kUpdateNorms) break;
         }
     } else {
         const long long groups = a.n - a.n_vec;
-        const long long stride = static_cast<long long>(gridDim.x - a.tiles_vec) * kTile;
-        for (long long base = (blockIdx.x - a.tiles_vec) * kTile; base < groups; base += stride) {
-            Tile<IN, 1, OP, HAS_H, STREAM, NORMS, THREADS, VPT, HALF, false>(a, a.n_vec, base + threadIdx.x, groups).run(sums);
+        const long long stride = static_cast<long long>(gridDim.x - a.groups_vec) * kTile;
+        for (long long base = (blockIdx.x - a.groups_vec) * kTile; base < groups; base += stride) {
+            Tile<IN, 1, OP, HAS_H, STREAM, NORMS, THREADS, VPT, HALF, false>(a, a.n_vec, base + threadIdx.x, groups, update_sums).run(sums);
         }
     }
-    if constexpr (NORMS) {
+    if constexpr (NORMS != kNoNorms) {
+        // One row of partial sums per workgroup: the two sums of the call, and
+        // for the update-norm variants one per committed update after them.
+        constexpr size_t kRow = NORMS == kUpdateNorms ? kUpdateNormRow : 2;
+        double *row = a.partials + kRow * static_cast<size_t>(blockIdx.x);
         double s0 = sums[0], s1 = sums[1];
         for (int off = 32; off > 0; off >>= 1) {
             s0 += __shfl_down(s0, off, 64);
             s1 += __shfl_down(s1, off, 64);
         }
         if (threadIdx.x == 0) {
-            a.partials[2 * static_cast<size_t>(blockIdx.x)] = s0;
-            a.partials[2 * static_cast<size_t>(blockIdx.x) + 1] = s1;
+            row[0] = s0;
+            row[1] = s1;
+        }
+        if constexpr (NORMS == kUpdateNorms) {
+            for (int t = 0; t < a.M; ++t) {
+                double u = update_sums[t * THREADS + threadIdx.x];
+                for (int off = 32; off > 0; off >>= 1) u += __shfl_down(u, off, 64);
+                if (threadIdx.x == 0) row[2 + t] = u;
+            }
         }
     }
 }
 
 // The kernel proper.  WAVES > 0 caps the wavefronts per SIMD at WAVES (the
 // register allocation is raised to match, so the hardware cannot place more).
-template <typename IN, int OP, bool HAS_H, int STREAM, bool NORMS, int THREADS, int VPT, int HALF,
+template <typename IN, int OP, bool HAS_H, int STREAM, int NORMS, int THREADS, int VPT, int HALF,
           int WAVES>
 __global__ __launch_bounds__(THREADS) void dense_kernel(const DenseArgs a)
 {
     dense_body<IN, OP, HAS_H, STREAM, NORMS, THREADS, VPT, HALF, WAVES>(a);
 }
 
-template <typename IN, int OP, bool HAS_H, int STREAM, bool NORMS, int THREADS, int VPT, int HALF>
+template <typename IN, int OP, bool HAS_H, int STREAM, int NORMS, int THREADS, int VPT, int HALF>
 __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void dense_kernel_one_wave(const DenseArgs a)
 {
@@ -579,6 +624,45 @@ bool finish_norms(double *partials, unsigned n_partials, size_t capacity, double
     }
     return launch_kernel(norms_finish_kernel, dim3(1), dim3(kFinishThreads), 0, stream, in, n_partials,
                          n_partials, out, n_out);
+}
+
+// The same for the rows of the update-norm variants: workgroup c sums column c
+// of the `rows` rows (lane i adds rows i, i + 256, ... in turn, then a tree over
+// the lanes).  Columns 0 and 1 are the sums of the call (column 1 is dropped when
+// n_main == 1), column 2 + t belongs to the t-th committed update.
+constexpr int kColumnThreads = 256;
+
+__global__ __launch_bounds__(kColumnThreads) void update_norms_finish_kernel(const double *partials,
+                                                                           unsigned rows,
+                                                                           double *main_out, int n_main,
+                                                                           double *update_out)
+{
+    __shared__ double tree[kColumnThreads];
+    const unsigned c = blockIdx.x;
+    double sum = 0.0;
+    for (unsigned r0 = threadIdx.x; r0 < rows; r0 += kColumnThreads * 8) {
+        double v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const unsigned r = r0 + u * kColumnThreads;
+            v[u] = r < rows ? partials[kUpdateNormRow * static_cast<size_t>(r) + c] : 0.0;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) sum += v[u];
+    }
+    tree[threadIdx.x] = sum;
+    __syncthreads();
+    for (int half = kColumnThreads / 2; half > 0; half >>= 1) {
+        if (threadIdx.x < static_cast<unsigned>(half)) tree[threadIdx.x] += tree[threadIdx.x + half];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        if (c >= 2) {
+            update_out[c - 2] = tree[0];
+        } else if (static_cast<int>(c) < n_main) {
+            main_out[c] = tree[0];
+        }
+    }
 }
 
 // Exact server-replica divergence (Sec. 3.3 / 5.3: bounded consistency keeps
@@ -661,6 +745,22 @@ unsigned xcd_count()
     return static_cast<unsigned>(n);
 }
 
+// Compute units of the current device, looked up once per device (0 when the
+// runtime cannot tell).
+unsigned cu_count()
+{
+    constexpr int kMaxDevices = 64;
+    static std::atomic<int> cached[kMaxDevices];
+    int device = 0;
+    if (hipGetDevice(&device) != hipSuccess || device < 0 || device >= kMaxDevices) return 0;
+    int n = cached[device].load(std::memory_order_relaxed);
+    if (n == 0) {
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess || n < 1) return 0;
+        cached[device].store(n, std::memory_order_relaxed);
+    }
+    return static_cast<unsigned>(n);
+}
+
 // Workgroups a launch of this shape uses (tiles of the 128-bit region plus the
 // workgroups of the element-wise region).
 template <typename IN, int THREADS, int VPT>
@@ -673,54 +773,75 @@ void count_workgroups(const DenseArgs &a, long long &n_vec, long long &tiles_v, 
     if (tiles_s > kMaxScalarGroups) tiles_s = kMaxScalarGroups;
 }
 
-template <typename IN, int OP, bool HAS_H, int STREAM, bool NORMS>
-mlf_status launch(DenseArgs &a, hipStream_t stream, double *norms_out, size_t partials_capacity)
+template <typename IN, int OP, bool HAS_H, int STREAM, int NORMS>
+mlf_status launch(DenseArgs &a, hipStream_t stream, double *norms_out, size_t partials_capacity,
+                  double *update_norms_out)
 {
     typedef Shape<IN, STREAM != 0, NORMS> S;
     static_assert(S::kWaves == 0 || S::kWaves == 1, "the cap is one wavefront per SIMD, or none");
-    static_assert(64 * S::kVpt * IN::kVec >= kMinTileElements || !NORMS, "a norms tile yields one partial pair");
+    static_assert(64 * S::kVpt * IN::kVec >= kMinTileElements || NORMS == kNoNorms, "a norms tile yields one partial pair");
     long long n_vec, tiles_v, tiles_s;
     count_workgroups<IN, S::kThreads, S::kVpt>(a, n_vec, tiles_v, tiles_s);
-    if (tiles_v + tiles_s > 0x7fffffffll) return MLF_EUNSUPPORTED;
-    if (NORMS && static_cast<size_t>(tiles_v + tiles_s) > partials_capacity) return MLF_EINVAL;
+    if (tiles_v > 0xffffffffll) return MLF_EUNSUPPORTED;
+    long long groups_v = tiles_v;
+    size_t lds = 0;
+    if constexpr (NORMS == kUpdateNorms) {
+        // As many workgroups (of one wavefront) as the device keeps resident:
+        // one per SIMD where the shape caps it at that, a few otherwise.
+        const long long resident = static_cast<long long>(cu_count()) * 4 * (S::kWaves == 1 ? 1 : 3);
+        const long long cap = resident < 1 ? 1024 : resident > kUpdateNormMaxGroups ? kUpdateNormMaxGroups : resident;
+        if (groups_v > cap) groups_v = cap;
+        lds = static_cast<size_t>(a.M) * S::kThreads * sizeof(double);
+    }
+    if (groups_v + tiles_s > 0x7fffffffll) return MLF_EUNSUPPORTED;
+    if (NORMS != kNoNorms && static_cast<size_t>(groups_v + tiles_s) > partials_capacity) return MLF_EINVAL;
     a.n_vec = n_vec;
     a.tiles_vec = static_cast<unsigned>(tiles_v);
+    a.groups_vec = static_cast<unsigned>(groups_v);
     a.xcds = xcd_count();
-    const unsigned grid = static_cast<unsigned>(tiles_v + tiles_s);
+    const unsigned grid = static_cast<unsigned>(groups_v + tiles_s);
     if (grid > 0) {
         bool ok;
         if constexpr (S::kWaves == 1) {
             ok = launch_kernel(dense_kernel_one_wave<IN, OP, HAS_H, STREAM, NORMS, S::kThreads, S::kVpt, S::kHalf>,
-                               dim3(grid), dim3(S::kThreads), 0, stream, a);
+                               dim3(grid), dim3(S::kThreads), lds, stream, a);
         } else {
             ok = launch_kernel(dense_kernel<IN, OP, HAS_H, STREAM, NORMS, S::kThreads, S::kVpt, S::kHalf, 0>,
-                               dim3(grid), dim3(S::kThreads), 0, stream, a);
+                               dim3(grid), dim3(S::kThreads), lds, stream, a);
         }
         if (!ok) return MLF_EHIP;
     }
-    if constexpr (NORMS) {
+    if constexpr (NORMS == kCallNorms) {
         if (!finish_norms(a.partials, grid, partials_capacity, norms_out, OP == kAggregate ? 1 : 2, stream)) {
+            return MLF_EHIP;
+        }
+    }
+    if constexpr (NORMS == kUpdateNorms) {
+        // (with no workgroup at all, n == 0, every sum is 0: rows = 0)
+        if (!launch_kernel(update_norms_finish_kernel, dim3(2 + static_cast<unsigned>(a.M)), dim3(kColumnThreads), 0,
+                           stream, a.partials, grid, norms_out, OP == kAggregate ? 1 : 2, update_norms_out)) {
             return MLF_EHIP;
         }
     }
     return MLF_OK;
 }
 
-template <typename IN, int OP, int STREAM, bool NORMS>
-mlf_status dispatch_state(DenseArgs &a, hipStream_t stream, double *norms_out, size_t capacity)
+template <typename IN, int OP, int STREAM, int NORMS>
+mlf_status dispatch_state(DenseArgs &a, hipStream_t stream, double *norms_out, size_t capacity,
+                          double *update_norms_out)
 {
     if constexpr (OP == kAggregate) {
-        return launch<IN, OP, false, STREAM, NORMS>(a, stream, norms_out, capacity);
+        return launch<IN, OP, false, STREAM, NORMS>(a, stream, norms_out, capacity, update_norms_out);
     } else {
         return a.momentum != nullptr
-                   ? launch<IN, OP, true, STREAM, NORMS>(a, stream, norms_out, capacity)
-                   : launch<IN, OP, false, STREAM, NORMS>(a, stream, norms_out, capacity);
+                   ? launch<IN, OP, true, STREAM, NORMS>(a, stream, norms_out, capacity, update_norms_out)
+                   : launch<IN, OP, false, STREAM, NORMS>(a, stream, norms_out, capacity, update_norms_out);
     }
 }
 
-template <int OP, bool NORMS = false>
+template <int OP, int NORMS = kNoNorms>
 mlf_status dispatch(DenseArgs &a, mlf_dtype dtype, hipStream_t stream, double *norms_out = nullptr,
-                    size_t capacity = 0)
+                    size_t capacity = 0, double *update_norms_out = nullptr)
 {
     // State that is too large to survive in the memory-side cache until the
     // next call is streamed through (no-reuse hint on its loads and stores);
@@ -732,11 +853,11 @@ mlf_status dispatch(DenseArgs &a, mlf_dtype dtype, hipStream_t stream, double *n
     if (a.out != nullptr) footprint += 4 * a.n;
     const bool streaming = OP == kAggregate || footprint > kInfinityCacheBytes;
     if (dtype == MLF_F32) {
-        return streaming ? dispatch_state<F32, OP, 3, NORMS>(a, stream, norms_out, capacity)
-                         : dispatch_state<F32, OP, 0, NORMS>(a, stream, norms_out, capacity);
+        return streaming ? dispatch_state<F32, OP, 3, NORMS>(a, stream, norms_out, capacity, update_norms_out)
+                         : dispatch_state<F32, OP, 0, NORMS>(a, stream, norms_out, capacity, update_norms_out);
     }
-    return streaming ? dispatch_state<BF16V4, OP, 3, NORMS>(a, stream, norms_out, capacity)
-                     : dispatch_state<BF16V8, OP, 0, NORMS>(a, stream, norms_out, capacity);
+    return streaming ? dispatch_state<BF16V4, OP, 3, NORMS>(a, stream, norms_out, capacity, update_norms_out)
+                     : dispatch_state<BF16V8, OP, 0, NORMS>(a, stream, norms_out, capacity, update_norms_out);
 }
 
 // Validates the arguments shared by the three dense calls and fills `a`.
@@ -909,15 +1030,29 @@ extern "C" size_t mlf_norms_workspace_bytes(int64_t n)
     return (norms_partials_capacity(n) + kFinishSlices) * 2 * sizeof(double);
 }
 
-extern "C" mlf_status mlf_aggregate_norm(const void *const *update_ptrs, int K, int64_t n,
-                                         mlf_dtype dtype, const int32_t *order, int n_order,
-                                         const float *weights, float *out, double *norm_sq,
-                                         void *workspace, size_t workspace_bytes,
-                                         mlf_stream stream)
+// Rows of partial sums an update-norm variant may need, whatever the device.
+static constexpr size_t update_norms_rows() { return static_cast<size_t>(kUpdateNormMaxGroups + kMaxScalarGroups); }
+
+extern "C" size_t mlf_update_norms_workspace_bytes(int64_t n)
 {
-    if (out == nullptr || norm_sq == nullptr) return MLF_EINVAL;
-    if (n >= 0 && (workspace == nullptr || workspace_bytes < mlf_norms_workspace_bytes(n))) return MLF_EINVAL;
-    if (reinterpret_cast<uintptr_t>(workspace) % 16 != 0 || reinterpret_cast<uintptr_t>(norm_sq) % 8 != 0) return MLF_EALIGN;
+    if (n < 0) return 0;
+    return update_norms_rows() * kUpdateNormRow * sizeof(double);
+}
+
+// mlf_aggregate_norm and mlf_aggregate_update_norms (update_norm_sq != NULL).
+static mlf_status aggregate_with_norms(const void *const *update_ptrs, int K, int64_t n, mlf_dtype dtype,
+                                       const int32_t *order, int n_order, const float *weights,
+                                       float *out, double *norm_sq, double *update_norm_sq,
+                                       bool per_update, void *workspace, size_t workspace_bytes,
+                                       mlf_stream stream)
+{
+    if (out == nullptr || norm_sq == nullptr || (per_update && update_norm_sq == nullptr)) return MLF_EINVAL;
+    const size_t need = per_update ? mlf_update_norms_workspace_bytes(n) : mlf_norms_workspace_bytes(n);
+    if (n >= 0 && (workspace == nullptr || workspace_bytes < need)) return MLF_EINVAL;
+    if (reinterpret_cast<uintptr_t>(workspace) % 16 != 0 || reinterpret_cast<uintptr_t>(norm_sq) % 8 != 0 ||
+        reinterpret_cast<uintptr_t>(update_norm_sq) % 8 != 0) {
+        return MLF_EALIGN;
+    }
     DenseArgs a;
     float *written[1] = {out};
     mlf_status st = prepare(a, update_ptrs, K, n, dtype, order, n_order, weights, written, 1);
@@ -929,22 +1064,47 @@ extern "C" mlf_status mlf_aggregate_norm(const void *const *update_ptrs, int K, 
     a.out = out;
     a.lr = 0.0f;
     a.mu = 0.0f;
-    return dispatch<kAggregate, true>(a, dtype, static_cast<hipStream_t>(stream), norm_sq,
-                                      norms_partials_capacity(n));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    return per_update ? dispatch<kAggregate, kUpdateNorms>(a, dtype, s, norm_sq, update_norms_rows(), update_norm_sq)
+                      : dispatch<kAggregate, kCallNorms>(a, dtype, s, norm_sq, norms_partials_capacity(n));
 }
 
-extern "C" mlf_status mlf_apply_grouped_norms(float *model, float *momentum,
-                                              const void *const *update_ptrs, int K, int64_t n,
-                                              mlf_dtype dtype, const int32_t *order, int n_order,
-                                              const float *weights, const int32_t *group_len,
-                                              int n_groups, float lr, float mu, double *norms_sq,
-                                              void *workspace, size_t workspace_bytes,
-                                              mlf_stream stream)
+extern "C" mlf_status mlf_aggregate_norm(const void *const *update_ptrs, int K, int64_t n,
+                                         mlf_dtype dtype, const int32_t *order, int n_order,
+                                         const float *weights, float *out, double *norm_sq,
+                                         void *workspace, size_t workspace_bytes,
+                                         mlf_stream stream)
 {
-    if (model == nullptr || norms_sq == nullptr) return MLF_EINVAL;
+    return aggregate_with_norms(update_ptrs, K, n, dtype, order, n_order, weights, out, norm_sq, nullptr,
+                                false, workspace, workspace_bytes, stream);
+}
+
+extern "C" mlf_status mlf_aggregate_update_norms(const void *const *update_ptrs, int K, int64_t n,
+                                                 mlf_dtype dtype, const int32_t *order, int n_order,
+                                                 const float *weights, float *out, double *norm_sq,
+                                                 double *update_norm_sq, void *workspace,
+                                                 size_t workspace_bytes, mlf_stream stream)
+{
+    return aggregate_with_norms(update_ptrs, K, n, dtype, order, n_order, weights, out, norm_sq,
+                                update_norm_sq, true, workspace, workspace_bytes, stream);
+}
+
+// mlf_apply_grouped_norms and mlf_apply_grouped_update_norms.
+static mlf_status apply_grouped_with_norms(float *model, float *momentum, const void *const *update_ptrs,
+                                           int K, int64_t n, mlf_dtype dtype, const int32_t *order,
+                                           int n_order, const float *weights, const int32_t *group_len,
+                                           int n_groups, float lr, float mu, double *norms_sq,
+                                           double *update_norm_sq, bool per_update, void *workspace,
+                                           size_t workspace_bytes, mlf_stream stream)
+{
+    if (model == nullptr || norms_sq == nullptr || (per_update && update_norm_sq == nullptr)) return MLF_EINVAL;
     if (n_groups < 0 || (n_groups > 0 && group_len == nullptr)) return MLF_EINVAL;
-    if (n >= 0 && (workspace == nullptr || workspace_bytes < mlf_norms_workspace_bytes(n))) return MLF_EINVAL;
-    if (reinterpret_cast<uintptr_t>(workspace) % 16 != 0 || reinterpret_cast<uintptr_t>(norms_sq) % 8 != 0) return MLF_EALIGN;
+    const size_t need = per_update ? mlf_update_norms_workspace_bytes(n) : mlf_norms_workspace_bytes(n);
+    if (n >= 0 && (workspace == nullptr || workspace_bytes < need)) return MLF_EINVAL;
+    if (reinterpret_cast<uintptr_t>(workspace) % 16 != 0 || reinterpret_cast<uintptr_t>(norms_sq) % 8 != 0 ||
+        reinterpret_cast<uintptr_t>(update_norm_sq) % 8 != 0) {
+        return MLF_EALIGN;
+    }
     DenseArgs a;
     float *written[2] = {model, momentum};
     mlf_status st = prepare(a, update_ptrs, K, n, dtype, order, n_order, weights, written, 2);
@@ -956,8 +1116,79 @@ extern "C" mlf_status mlf_apply_grouped_norms(float *model, float *momentum,
     a.out = nullptr;
     a.lr = lr;
     a.mu = mu;
-    return dispatch<kApplyGrouped, true>(a, dtype, static_cast<hipStream_t>(stream), norms_sq,
-                                         norms_partials_capacity(n));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    return per_update ? dispatch<kApplyGrouped, kUpdateNorms>(a, dtype, s, norms_sq, update_norms_rows(), update_norm_sq)
+                      : dispatch<kApplyGrouped, kCallNorms>(a, dtype, s, norms_sq, norms_partials_capacity(n));
+}
+
+extern "C" mlf_status mlf_apply_grouped_norms(float *model, float *momentum,
+                                              const void *const *update_ptrs, int K, int64_t n,
+                                              mlf_dtype dtype, const int32_t *order, int n_order,
+                                              const float *weights, const int32_t *group_len,
+                                              int n_groups, float lr, float mu, double *norms_sq,
+                                              void *workspace, size_t workspace_bytes,
+                                              mlf_stream stream)
+{
+    return apply_grouped_with_norms(model, momentum, update_ptrs, K, n, dtype, order, n_order, weights,
+                                    group_len, n_groups, lr, mu, norms_sq, nullptr, false, workspace,
+                                    workspace_bytes, stream);
+}
+
+extern "C" mlf_status mlf_apply_grouped_update_norms(float *model, float *momentum,
+                                                     const void *const *update_ptrs, int K, int64_t n,
+                                                     mlf_dtype dtype, const int32_t *order, int n_order,
+                                                     const float *weights, const int32_t *group_len,
+                                                     int n_groups, float lr, float mu, double *norms_sq,
+                                                     double *update_norm_sq, void *workspace,
+                                                     size_t workspace_bytes, mlf_stream stream)
+{
+    return apply_grouped_with_norms(model, momentum, update_ptrs, K, n, dtype, order, n_order, weights,
+                                    group_len, n_groups, lr, mu, norms_sq, update_norm_sq, true, workspace,
+                                    workspace_bytes, stream);
+}
+
+// The scheduler's upper bound of the divergence a batch causes (Sec. 5.3),
+// from the norms the calls above return: Eq. 2 unrolled over the batch's server
+// steps gives w_after - w_before = (mu + ... + mu^S) h0 + sum_j c_j u_j with
+// c_j = 1 + mu + ... + mu^(S-j), and u_j = -lr * (sum over group j of wt * g);
+// the triangle inequality bounds the norm of the whole and of every u_j.  Host
+// arithmetic only.
+extern "C" mlf_status mlf_divergence_bound(double h_norm_sq, const double *update_norm_sq,
+                                           const int32_t *order, int n_order, int K,
+                                           const float *weights, const int32_t *group_len,
+                                           int n_groups, float lr, float mu, double *bound)
+{
+    if (bound == nullptr || K < 1 || n_order < 0 || n_order > K || n_groups < 0) return MLF_EINVAL;
+    if (K > MLF_MAX_K) return MLF_EUNSUPPORTED;
+    if (n_order > 0 && (update_norm_sq == nullptr || order == nullptr)) return MLF_EINVAL;
+    if (n_groups > 0 && group_len == nullptr) return MLF_EINVAL;
+    if (!(h_norm_sq >= 0.0)) return MLF_EINVAL;
+    long long covered = 0;
+    for (int j = 0; j < n_groups; ++j) {
+        if (group_len[j] < 1 || covered + group_len[j] > n_order) return MLF_EINVAL;
+        covered += group_len[j];
+    }
+    if (covered != n_order) return MLF_EINVAL;
+    for (int t = 0; t < n_order; ++t) {
+        if (order[t] < 0 || order[t] >= K || !(update_norm_sq[t] >= 0.0)) return MLF_EINVAL;
+    }
+    const double gamma = static_cast<double>(mu), eta = static_cast<double>(lr);
+    // suffix[j] = 1 + gamma + ... + gamma^(S-1-j); the history's coefficient is gamma * suffix[0]
+    double suffix[MLF_MAX_K + 1];
+    suffix[n_groups] = 0.0;
+    for (int j = n_groups - 1; j >= 0; --j) suffix[j] = 1.0 + gamma * suffix[j + 1];
+    double total = __builtin_fabs(gamma * suffix[0]) * __builtin_sqrt(h_norm_sq);
+    int t = 0;
+    for (int j = 0; j < n_groups; ++j) {
+        double step = 0.0;
+        for (int i = 0; i < group_len[j]; ++i, ++t) {
+            const double wt = weights != nullptr ? static_cast<double>(weights[order[t]]) : 1.0;
+            step += __builtin_fabs(wt) * __builtin_sqrt(update_norm_sq[t]);
+        }
+        total += __builtin_fabs(suffix[j]) * __builtin_fabs(eta) * step;
+    }
+    *bound = total;
+    return MLF_OK;
 }
 
 // Squared distance of two vectors with the partial sums in `partials` (room for

@@ -25,7 +25,8 @@ def test_every_declared_symbol_is_exported():
     assert {"mlf_aggregate", "mlf_apply_ordered", "mlf_aggregate_apply", "mlf_apply_grouped",
             "mlf_sparse_scatter_add", "mlf_sparse_workspace_bytes", "mlf_aggregate_norm",
             "mlf_apply_grouped_norms", "mlf_norms_workspace_bytes", "mlf_divergence", "mlf_divergence_static",
-            "mlf_counts_add_dense",
+            "mlf_counts_add_dense", "mlf_aggregate_update_norms", "mlf_apply_grouped_update_norms",
+            "mlf_update_norms_workspace_bytes", "mlf_divergence_bound",
             "mlf_status_string"} <= set(names)
     lib = ctypes.CDLL(mlf.library_path())
     for name in names:
@@ -205,3 +206,82 @@ def test_divergence_static_argument_checks():
     assert lib.mlf_divergence_static(a, b, 8, out + 4, None) == B.MLF_EALIGN
     text = open(os.path.join(ROOT, "include", "mlfabric.h")).read()
     assert re.search(r"#define MLF_STATIC_MAX_N \(1ll << 28\)", text) and B.MLF_STATIC_MAX_N == 1 << 28
+
+
+def test_update_norms_argument_checks():
+    lib = B.raw()
+    u0, u1, w, h, out = FAKE, FAKE + 0x100000, FAKE + 0x200000, FAKE + 0x300000, FAKE + 0x400000
+    norms, per_update, ws = FAKE + 0x500000, FAKE + 0x500100, FAKE + 0x600000
+    need = mlf.mlf_update_norms_workspace_bytes(8)
+    assert need > 0 and need == mlf.mlf_update_norms_workspace_bytes(10 ** 9) and need < 8 << 20
+    assert mlf.mlf_update_norms_workspace_bytes(-1) == 0
+    o, m = order(0, 1)
+    g = (ctypes.c_int32 * 2)(1, 1)
+
+    def agg_call(out=out, norms=norms, per_update=per_update, ws=ws, nbytes=need, n=0):
+        return lib.mlf_aggregate_update_norms(tab(u0, u1), 2, n, 0, o, m, None, out, norms, per_update,
+                                              ws, nbytes, None)
+
+    assert agg_call(per_update=None) == B.MLF_EINVAL
+    assert agg_call(norms=None) == B.MLF_EINVAL
+    assert agg_call(out=None) == B.MLF_EINVAL
+    assert agg_call(ws=None) == B.MLF_EINVAL
+    assert agg_call(nbytes=need - 1) == B.MLF_EINVAL
+    assert agg_call(per_update=per_update + 4) == B.MLF_EALIGN
+    assert agg_call(ws=ws + 8) == B.MLF_EALIGN
+
+    def grouped_call(model=w, norms=norms, per_update=per_update, ws=ws, nbytes=need, lens=g, n_groups=2):
+        return lib.mlf_apply_grouped_update_norms(model, h, tab(u0, u1), 2, 8, 0, o, m, None, lens, n_groups,
+                                                  0.1, 0.9, norms, per_update, ws, nbytes, None)
+
+    assert grouped_call(per_update=None) == B.MLF_EINVAL
+    assert grouped_call(model=None) == B.MLF_EINVAL
+    assert grouped_call(nbytes=16) == B.MLF_EINVAL
+    assert grouped_call(n_groups=1) == B.MLF_EINVAL            # does not cover the order
+    assert grouped_call(norms=norms + 4) == B.MLF_EALIGN
+
+
+def test_divergence_bound_against_the_oracle_and_its_argument_checks():
+    import math
+
+    import oracle
+    rng = np.random.default_rng(31)
+    for trial in range(50):
+        K = int(rng.integers(1, 20))
+        M = int(rng.integers(0, K + 1))
+        order_ = [int(i) for i in rng.permutation(K)[:M]]
+        groups, left = [], M
+        while left > 0:
+            ln = int(rng.integers(1, left + 1))
+            groups.append(ln)
+            left -= ln
+        weights = rng.uniform(-2, 2, K).astype(np.float32) if trial % 3 else None
+        lr, mu = float(np.float32(rng.uniform(0.001, 0.5))), float(np.float32(rng.uniform(0, 0.99)))
+        h_sq = float(rng.uniform(0, 10))
+        u_sq = rng.uniform(0, 100, M)
+        got = mlf.mlf_divergence_bound(h_sq, u_sq, order_, K, weights, groups, lr, mu)
+        in_sequence = weights[order_] if weights is not None else None
+        want = oracle.divergence_bound(math.sqrt(h_sq), np.sqrt(u_sq), in_sequence, groups, lr, mu)
+        assert abs(got - want) <= 1e-13 * max(abs(want), 1e-300), (trial, got, want)
+    # the two-update case of Sec. 3.3 with dyadic numbers: (g + g^2) ||h0|| + (1 + g) ||u1|| + ||u2||
+    assert mlf.mlf_divergence_bound(9.0, [25.0, 49.0], [1, 0], 2, None, [1, 1], 0.25, 0.5) == \
+        0.75 * 3 + 1.5 * 0.25 * 5 + 0.25 * 7
+    lib = B.raw()
+    out = ctypes.c_double()
+    o, m = order(0, 1)
+    u = (ctypes.c_double * 2)(1.0, 2.0)
+    g = (ctypes.c_int32 * 2)(1, 1)
+
+    def call(h=1.0, u=u, o=o, m=m, K=2, g=g, n_groups=2, out=ctypes.byref(out)):
+        return lib.mlf_divergence_bound(h, u, o, m, K, None, g, n_groups, 0.1, 0.9, out)
+
+    assert call() == B.MLF_OK
+    assert call(out=None) == B.MLF_EINVAL
+    assert call(h=-1.0) == B.MLF_EINVAL and call(h=float("nan")) == B.MLF_EINVAL
+    assert call(u=(ctypes.c_double * 2)(1.0, -2.0)) == B.MLF_EINVAL
+    assert call(u=None) == B.MLF_EINVAL
+    assert call(n_groups=1) == B.MLF_EINVAL
+    assert call(g=(ctypes.c_int32 * 2)(2, 0)) == B.MLF_EINVAL
+    assert call(o=order(0, 5)[0]) == B.MLF_EINVAL
+    assert call(K=65) == B.MLF_EUNSUPPORTED
+    assert call(m=0, n_groups=0) == B.MLF_OK and out.value == 0.0

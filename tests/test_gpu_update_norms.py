@@ -1,0 +1,166 @@
+"""GPU parity of the calls that also return the squared norm of every committed
+update (Table 1 of the paper: a push carries update_norm; Sec. 5.3: the scheduler
+bounds the divergence from these norms).
+
+Data outputs must equal the oracle's bit for bit.  Every norm is a binary64 sum
+of exact squares in a fixed order (per lane over its tiles, a tree over the
+lanes, then a fixed-order sum over the workgroups) against the oracle's exactly
+rounded sum: a lane adds at most a few thousand terms here, so the two differ by
+well under 1e-12 relative, the tolerance of these tests.  The GPU's sums must
+repeat bit for bit from run to run.  The scheduler's bound formed from the GPU's
+norms must dominate the exact divergence the same call returns."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_1907_00434_amd as mlf
+import workloads as W
+from parity import assert_same_bits
+
+pytestmark = pytest.mark.gpu
+RTOL = 1e-12
+
+
+def close(got, ref):
+    return abs(got - ref) <= RTOL * max(abs(ref), 1e-300)
+
+
+def workspace(n):
+    return torch.empty(mlf.mlf_update_norms_workspace_bytes(n), dtype=torch.uint8, device="cuda")
+
+
+def bits_or_values(u):
+    """Host copy an oracle norm accepts: float32 values, or bfloat16 bit patterns."""
+    if u.dtype == torch.bfloat16:
+        return u.view(torch.int16).cpu().numpy().view(np.uint16)
+    return u.cpu().numpy()
+
+
+def groups_for(M, seed):
+    rng = np.random.default_rng(seed)
+    lens = [1] * int(rng.integers(0, M + 1))
+    left = M - len(lens)
+    while left > 0:
+        ln = int(rng.integers(1, left + 1))
+        lens.append(ln)
+        left -= ln
+    return lens
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("n,K", [(1, 1), (7, 3), (257, 5), (4099, 8), (700_003, 17), (2_000_001, 64)])
+def test_aggregate_update_norms(dtype, n, K):
+    cfg = W.scaled(W.CONFIGS["cfg2"], n=n, K=K, dtype=dtype)
+    d = W.dense_inputs(cfg, "cuda", n_dropped=K // 4)
+    ups_h = [W.to_host(u) for u in d["updates"]]
+    M = len(d["order"])
+    out = torch.empty(n, device="cuda")
+    norm = torch.full((1,), -1.0, dtype=torch.float64, device="cuda")
+    per_update = torch.full((M,), -1.0, dtype=torch.float64, device="cuda")
+    ws = workspace(n)
+    mlf.mlf_aggregate_update_norms(d["updates"], d["order"], d["weights"], out, norm, per_update, ws)
+    ref = oracle.aggregate(ups_h, d["order"], d["weights"])
+    assert_same_bits(out, ref, "aggregate_update_norms out")
+    first, firsts = norm.item(), per_update.cpu().numpy().copy()
+    assert close(first, oracle.sum_sq(ref)), (first, oracle.sum_sq(ref))
+    for t, j in enumerate(d["order"]):
+        want = oracle.sum_sq(bits_or_values(d["updates"][int(j)][:n]))
+        assert close(firsts[t], want), (t, firsts[t], want)
+    norm.fill_(-1.0)
+    per_update.fill_(-1.0)
+    mlf.mlf_aggregate_update_norms(d["updates"], d["order"], d["weights"], out, norm, per_update, ws)
+    assert norm.item() == first                                   # reproducible bit for bit
+    assert np.array_equal(per_update.cpu().numpy(), firsts)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("n,K", [(1, 1), (9, 3), (4099, 8), (300_001, 16), (70_001, 33), (1_000_003, 64)])
+def test_apply_grouped_update_norms_and_the_bound(dtype, n, K):
+    cfg = W.scaled(W.CONFIGS["cfg2"], n=n, K=K, dtype=dtype)
+    d = W.dense_inputs(cfg, "cuda", momentum_init="random", n_dropped=K // 5)
+    d["weights"] = np.random.default_rng(K).uniform(0.1, 2.0, K).astype(np.float32)
+    M = len(d["order"])
+    lens = groups_for(M, K * 7 + n)
+    ups_h = [W.to_host(u) for u in d["updates"]]
+    w0, h0 = W.to_host(d["model"]), W.to_host(d["momentum"])
+    w_h, h_h = w0.copy(), h0.copy()
+    oracle.apply_grouped(w_h, h_h, ups_h, d["order"], d["weights"], lens, d["lr"], d["mu"])
+    norms = torch.full((2,), -1.0, dtype=torch.float64, device="cuda")
+    per_update = torch.full((M,), -1.0, dtype=torch.float64, device="cuda")
+    model, momentum = d["model"].clone(), d["momentum"].clone()
+    mlf.mlf_apply_grouped_update_norms(model, momentum, d["updates"], d["order"], d["weights"], lens,
+                                       d["lr"], d["mu"], norms, per_update, workspace(n))
+    assert_same_bits(model, w_h, "model")
+    assert_same_bits(momentum, h_h, "momentum")
+    got, got_updates = norms.cpu().numpy(), per_update.cpu().numpy()
+    assert close(got[0], oracle.sum_sq(h_h)), (got[0], oracle.sum_sq(h_h))
+    assert close(got[1], oracle.sum_sq_diff(w_h, w0)), (got[1], oracle.sum_sq_diff(w_h, w0))
+    for t, j in enumerate(d["order"]):
+        want = oracle.sum_sq(bits_or_values(d["updates"][int(j)][:n]))
+        assert close(got_updates[t], want), (t, got_updates[t], want)
+    # the scheduler's bound from these norms and the history's norm before the batch
+    bound = mlf.mlf_divergence_bound(oracle.sum_sq(h0), got_updates, d["order"], K, d["weights"], lens,
+                                     d["lr"], d["mu"])
+    assert math.sqrt(got[1]) <= bound * (1 + 1e-5), (math.sqrt(got[1]), bound)
+
+
+def test_streamed_state_and_the_full_batch_of_32_updates():
+    """Model + momentum above 256 MiB (the streamed, one-wavefront-per-SIMD
+    shape), 32 committed updates: 8 forwarded directly, three groups of 8."""
+    n = 36_000_003
+    cfg = W.scaled(W.CONFIGS["cfg3"], n=n)
+    d = W.dense_inputs(cfg, "cuda", momentum_init="random")
+    M = len(d["order"])
+    assert M == 32 and 8 * n > 256 << 20
+    weights = np.full(cfg.K, 0.125, np.float32)
+    weights[d["order"][:8]] = 1.0
+    lens = [1] * 8 + [8, 8, 8]
+    ups_h = [W.to_host(u) for u in d["updates"]]
+    w0, h0 = W.to_host(d["model"]), W.to_host(d["momentum"])
+    w_h, h_h = w0.copy(), h0.copy()
+    oracle.apply_grouped(w_h, h_h, ups_h, d["order"], weights, lens, d["lr"], d["mu"], threads=16)
+    norms = torch.zeros(2, dtype=torch.float64, device="cuda")
+    per_update = torch.zeros(M, dtype=torch.float64, device="cuda")
+    mlf.mlf_apply_grouped_update_norms(d["model"], d["momentum"], d["updates"], d["order"], weights, lens,
+                                       d["lr"], d["mu"], norms, per_update, workspace(n))
+    assert_same_bits(d["model"], w_h, "model")
+    assert_same_bits(d["momentum"], h_h, "momentum")
+    got, got_updates = norms.cpu().numpy(), per_update.cpu().numpy()
+    assert close(got[0], oracle.sum_sq(h_h, threads=16))
+    assert close(got[1], oracle.sum_sq_diff(w_h, w0, threads=16))
+    for t, j in enumerate(d["order"]):
+        assert close(got_updates[t], oracle.sum_sq(ups_h[int(j)], threads=16)), t
+    bound = mlf.mlf_divergence_bound(oracle.sum_sq(h0, threads=16), got_updates, d["order"], cfg.K, weights,
+                                     lens, d["lr"], d["mu"])
+    assert math.sqrt(got[1]) <= bound * (1 + 1e-5)
+    del d, ups_h
+    torch.cuda.empty_cache()
+
+
+def test_no_committed_update_and_unaligned_vectors():
+    cfg = W.scaled(W.CONFIGS["cfg2"], n=10_001, K=4)
+    d = W.dense_inputs(cfg, "cuda", momentum_init="random")
+    ws = workspace(cfg.n)
+    # nothing committed: the model stays, the norms describe it, no update norm is written
+    norms = torch.full((2,), -1.0, dtype=torch.float64, device="cuda")
+    per_update = torch.full((1,), -7.0, dtype=torch.float64, device="cuda")
+    model, momentum = d["model"].clone(), d["momentum"].clone()
+    mlf.mlf_apply_grouped_update_norms(model, momentum, d["updates"], [], None, [], d["lr"], d["mu"], norms,
+                                       per_update, ws)
+    assert torch.equal(model, d["model"]) and torch.equal(momentum, d["momentum"])
+    assert close(norms[0].item(), oracle.sum_sq(W.to_host(d["momentum"]))) and norms[1].item() == 0.0
+    assert per_update.item() == -7.0
+    # element-wise path: vectors that start 4 bytes past a 16-byte boundary
+    ups = [u[1:] for u in d["updates"]]
+    out = torch.empty(cfg.n, device="cuda")[1:]
+    norm = torch.zeros(1, dtype=torch.float64, device="cuda")
+    per_update = torch.zeros(4, dtype=torch.float64, device="cuda")
+    mlf.mlf_aggregate_update_norms(ups, d["order"], d["weights"], out, norm, per_update, ws)
+    ref = oracle.aggregate([W.to_host(u) for u in ups], d["order"], d["weights"])
+    assert_same_bits(out, ref, "out")
+    assert close(norm.item(), oracle.sum_sq(ref))
+    for t, j in enumerate(d["order"]):
+        assert close(per_update[t].item(), oracle.sum_sq(W.to_host(ups[int(j)])))
