@@ -85,11 +85,13 @@ class DenseJob:
             self.out = torch.empty(cfg.n, device="cuda:0")
         with_h = 16 if d["momentum"] is not None else 8
         state = {"aggregate": 4, "apply_ordered": with_h, "aggregate_apply": with_h,
-                 "apply_grouped": with_h, "apply_grouped_norms": with_h}[self.call]
-        if self.call == "apply_grouped_norms":
+                 "apply_grouped": with_h, "apply_grouped_norms": with_h,
+                 "apply_grouped_update_norms": with_h}[self.call]
+        if self.call in ("apply_grouped_norms", "apply_grouped_update_norms"):
             self.norms = torch.zeros(2, dtype=torch.float64, device="cuda:0")
-            self.norm_ws = torch.empty(mlf.mlf_norms_workspace_bytes(cfg.n), dtype=torch.uint8,
-                                       device="cuda:0")
+            self.update_norms = torch.zeros(len(d["order"]), dtype=torch.float64, device="cuda:0")
+            nbytes = max(mlf.mlf_norms_workspace_bytes(cfg.n), mlf.mlf_update_norms_workspace_bytes(cfg.n))
+            self.norm_ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda:0")
         # a scheduled batch: a quarter of the updates forwarded directly, the rest
         # in three aggregated groups (Sec. 5.2 of the paper)
         M = len(d["order"])
@@ -112,6 +114,10 @@ class DenseJob:
             m.mlf_apply_grouped_norms(d["model"], d["momentum"], d["updates"], d["order"],
                                       d["weights"], self.group_len, d["lr"], d["mu"], self.norms,
                                       self.norm_ws)
+        elif self.call == "apply_grouped_update_norms":
+            m.mlf_apply_grouped_update_norms(d["model"], d["momentum"], d["updates"], d["order"],
+                                             d["weights"], self.group_len, d["lr"], d["mu"], self.norms,
+                                             self.update_norms, self.norm_ws)
         else:
             m.mlf_aggregate_apply(d["model"], d["momentum"], None, d["updates"], d["order"],
                                   d["weights"], d["lr"], d["mu"])
@@ -389,9 +395,11 @@ def main():
         torch.cuda.empty_cache()
         rows = {}
         dense_frac = {}
+        extension_frac = {}      # the variants that also return one norm per update
         plan = [("cfg1", None), ("cfg2", "aggregate"), ("cfg2", None), ("cfg3", None),
                 ("cfg3", "apply_grouped"), ("cfg2", "apply_grouped"),
                 ("cfg2", "apply_grouped_norms"), ("cfg3", "apply_grouped_norms"),
+                ("cfg2", "apply_grouped_update_norms"), ("cfg3", "apply_grouped_update_norms"),
                 ("cfg3", "divergence"), ("cfg4", None), ("cfg5", None), ("cfg5", "permuted"), ("cfg5", "counts_add_dense")]
         for name, call in plan:
             j = make(name, call)
@@ -410,7 +418,10 @@ def main():
                 rows[key]["cells_with_nonzero_sum"] = j.changed_cells
                 rows[key]["GB/s_at_nominal_bytes (every cell read and written)"] = round(j.bytes_nominal / ev / 1e6, 1)
             if isinstance(j, DenseJob) and name != "cfg1":
-                dense_frac[key] = rows[key]["frac_of_peak"]
+                if j.call.endswith("update_norms"):
+                    extension_frac[key] = rows[key]["frac_of_peak"]
+                else:
+                    dense_frac[key] = rows[key]["frac_of_peak"]
             if name in ("cfg1", "cfg2") and call is None:
                 # The state of cfg1 / cfg2 fits the caches: also time the call after a
                 # read-only pass over 2 GiB, which evicts L2 and the memory-side cache
@@ -462,6 +473,8 @@ def main():
             "frac": dense_frac,
             "min_dense_frac": dense_frac[weakest],
             "min_dense_row": weakest,
+            "per_update_norm_variants (binary64 work per update element on top of the pass; "
+            "not counted in min_dense_frac)": extension_frac,
         }
 
     print(json.dumps(line))

@@ -316,16 +316,20 @@ struct Tile {
             if constexpr (NORMS == kUpdateNorms) {
                 // The update as it arrived (before its weight); a binary32 square
                 // is exact in binary64.  Lanes without an element hold zeros.
+                // (The fused multiply-add rounds once, as the separate addition
+                // of the exact product would: the same bits, half the instructions.)
                 double sq = 0.0;
 #pragma unroll
                 for (int v = 0; v < VPT; ++v) {
 #pragma unroll
                     for (int j = 0; j < W; ++j) {
                         const double xx = x[c][v][j];
-                        sq += xx * xx;
+                        sq = __builtin_fma(xx, xx, sq);
                     }
                 }
-                update_sums[t * THREADS + threadIdx.x] += sq;       // the lane's own slot
+                // the lane's own slot: an LDS add that returns nothing, so nothing waits for it
+                __hip_atomic_fetch_add(&update_sums[t * THREADS + threadIdx.x], sq, __ATOMIC_RELAXED,
+                                       __HIP_MEMORY_SCOPE_WORKGROUP);
             }
 #pragma unroll
             for (int v = 0; v < VPT; ++v) {

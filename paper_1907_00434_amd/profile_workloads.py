@@ -6,7 +6,8 @@ the benchmark around it.
     python3 -m paper_1907_00434_amd.profile_workloads [--reps N] cfg3 cfg5 ...
 
 cfg2 / cfg4: aggregate_apply (cfg2 also the plain aggregate and the grouped apply
-with norms); cfg3: apply_ordered, apply_grouped, apply_grouped_norms, divergence;
+with norms and with per-update norms); cfg3: apply_ordered, apply_grouped,
+apply_grouped_norms, apply_grouped_update_norms, divergence;
 cfg5: sparse_scatter_add with word id = rank - 1, then with the ids permuted;
 copy: a plain 1 GiB device copy (the reference for byte counters).
 """
@@ -72,6 +73,12 @@ def main():
                 for _ in range(args.reps):
                     mlf.mlf_apply_grouped_norms(d["model"], d["momentum"], d["updates"], d["order"],
                                                 d["weights"], groups, d["lr"], d["mu"], norms, ws)
+                per_update = torch.zeros(M, dtype=torch.float64, device=dev)
+                ws2 = torch.empty(mlf.mlf_update_norms_workspace_bytes(cfg.n), dtype=torch.uint8, device=dev)
+                for _ in range(args.reps):
+                    mlf.mlf_apply_grouped_update_norms(d["model"], d["momentum"], d["updates"], d["order"],
+                                                       d["weights"], groups, d["lr"], d["mu"], norms,
+                                                       per_update, ws2)
             if name == "cfg2":
                 out = torch.empty(cfg.n, device=dev)
                 for _ in range(args.reps):
