@@ -171,6 +171,24 @@ class DivergenceJob:
         self.mlf.mlf_divergence(self.a, self.b, self.dist, self.ws)
 
 
+class TrafficMixJob:
+    """A reference for cfg4's traffic mix: mlf_aggregate of three binary32 updates
+    of cfg4's length reads 12 bytes and writes 4 per element (a quarter of the
+    traffic is stores, as in cfg4's 16 read + 16 read-modify-write bytes), with
+    128-bit loads throughout and nothing read back."""
+
+    def __init__(self, cfg, mlf, torch):
+        self.cfg, self.mlf, self.call = cfg, mlf, "aggregate of 3 binary32 updates (traffic-mix reference)"
+        g = torch.Generator(device="cuda:0")
+        g.manual_seed(cfg.seed)
+        self.ups = [torch.randn(cfg.n, generator=g, device="cuda:0") for _ in range(3)]
+        self.out = torch.empty(cfg.n, device="cuda:0")
+        self.bytes, self.units = 16 * cfg.n, 3 * cfg.n
+
+    def step(self):
+        self.mlf.mlf_aggregate(self.ups, [0, 1, 2], None, self.out)
+
+
 class DenseDeltaJob:
     """The LDA update as 8 dense int32 delta matrices (2 % of the cells non-zero).
     Bytes: every delta matrix once, and one read and one write of the cells
@@ -325,6 +343,8 @@ def main():
             return DivergenceJob(cfg, mlf, torch)
         if call == "counts_add_dense":
             return DenseDeltaJob(cfg, mlf, torch)
+        if call == "traffic_mix":
+            return TrafficMixJob(cfg, mlf, torch)
         if isinstance(cfg, W.SparseConfig):
             return SparseJob(cfg, mlf, W, torch, permute_ids=(call == "permuted" or args.permute_ids))
         return DenseJob(cfg, mlf, W, torch, call)
@@ -400,7 +420,7 @@ def main():
                 ("cfg3", "apply_grouped"), ("cfg2", "apply_grouped"),
                 ("cfg2", "apply_grouped_norms"), ("cfg3", "apply_grouped_norms"),
                 ("cfg2", "apply_grouped_update_norms"), ("cfg3", "apply_grouped_update_norms"),
-                ("cfg3", "divergence"), ("cfg4", None), ("cfg5", None), ("cfg5", "permuted"), ("cfg5", "counts_add_dense")]
+                ("cfg3", "divergence"), ("cfg4", None), ("cfg4", "traffic_mix"), ("cfg5", None), ("cfg5", "permuted"), ("cfg5", "counts_add_dense")]
         for name, call in plan:
             j = make(name, call)
             _, ev = time_steps(torch, j, 20, 3)

@@ -174,9 +174,11 @@ mlf_status mlf_apply_grouped(float *model, float *momentum,
  * so a call repeated with the same arguments on the same device gives the same
  * bits.  The order depends on n, on the data type of the updates, on whether
  * every pointer of the call is 16-byte aligned (128-bit or element-wise path),
- * on whether momentum is given and whether 4n bytes per written vector exceed
- * 256 MiB in total (these select the tile shape), and on the number of XCDs of
- * the device; calls that differ in any of these may differ in the last bits.
+ * on whether momentum is given, whether 4n bytes per written vector exceed
+ * 256 MiB in total and, if so, whether 16 or more updates (20 or more for the
+ * aggregate) are committed (these select the tile shape), and on the number of
+ * XCDs of the device; calls that differ in any of these may differ in the last
+ * bits.
  * The sums agree with the exactly rounded ones to about 1e-14 relative.
  *
  *   norm_sq / norms_sq  device, 1 / 2 doubles, 8-byte aligned; written

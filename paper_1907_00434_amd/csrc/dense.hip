@@ -120,7 +120,8 @@ struct BF16V4 {
 // block are issued before the current one is consumed.  WAVES = 1 caps the
 // wavefronts per SIMD at one.  The values are the best of sweeps on MI355X:
 //
-//  - binary32 updates, state streamed (more than the memory-side cache holds):
+//  - binary32 updates, state streamed (more than the memory-side cache holds),
+//    MANY updates committed (16 or more; 20 or more for the plain aggregate):
 //    ONE wavefront per SIMD and the narrowest tile (one 128-bit group per lane,
 //    1 KiB per vector and wavefront).  The fewer and the narrower the tiles in
 //    flight, the shorter the stretch of every vector that the chip works on at
@@ -129,28 +130,36 @@ struct BF16V4 {
 //    with three wavefronts per SIMD and 2 KiB tiles; the same loads without the
 //    stores run at 7.1 TB/s either way).  Spreading the tiles in flight over 16
 //    distant regions costs 6 %; tiles of 512 bytes per vector lose 10-25 %;
+//  - the same with FEW updates: a single wavefront per SIMD then has too few
+//    loads in flight (an ordered apply of 1 to 6 updates ran at 3.2-4.4 TB/s
+//    in that shape), so the wide tile and the uncapped occupancy are used:
+//    6.2-6.5 TB/s from 1 to 8 updates; the shapes cross between 12 and 16;
 //  - bfloat16 updates, state streamed: a quarter of the traffic is stores and
 //    64-bit update loads cover only 512 bytes per wavefront, so the wider tile
 //    and the uncapped occupancy are kept (6.4 TB/s; the narrow capped shape
 //    drops to 3.4 TB/s);
 //  - state that stays cached between calls: wider tiles, no cap.
-template <typename IN, bool STREAMED, int NORMS>
+template <typename IN, bool STREAMED, int NORMS, bool MANY>
 struct Shape;
 
 template <int NORMS>
-struct Shape<F32, true, NORMS> {     // streamed state, binary32 updates
+struct Shape<F32, true, NORMS, true> {      // streamed state, binary32, many updates
     static constexpr int kThreads = 64, kVpt = 1, kHalf = 8, kWaves = 1;
 };
 template <int NORMS>
-struct Shape<BF16V4, true, NORMS> {  // streamed state, bfloat16 updates
-    static constexpr int kThreads = 64, kVpt = 2, kHalf = 4, kWaves = 0;
-};
-template <int NORMS>
-struct Shape<F32, false, NORMS> {    // cached state, binary32 updates
+struct Shape<F32, true, NORMS, false> {     // streamed state, binary32, few updates
     static constexpr int kThreads = 64, kVpt = 2, kHalf = 8, kWaves = 0;
 };
-template <int NORMS>
-struct Shape<BF16V8, false, NORMS> { // cached state, bfloat16 updates; with norms one wavefront per workgroup
+template <int NORMS, bool MANY>
+struct Shape<BF16V4, true, NORMS, MANY> {   // streamed state, bfloat16 updates
+    static constexpr int kThreads = 64, kVpt = 2, kHalf = 4, kWaves = 0;
+};
+template <int NORMS, bool MANY>
+struct Shape<F32, false, NORMS, MANY> {     // cached state, binary32 updates
+    static constexpr int kThreads = 64, kVpt = 2, kHalf = 8, kWaves = 0;
+};
+template <int NORMS, bool MANY>
+struct Shape<BF16V8, false, NORMS, MANY> {  // cached state, bfloat16 updates; with norms one wavefront per workgroup
     static constexpr int kThreads = NORMS != 0 ? 64 : 256, kVpt = NORMS != 0 ? 2 : 1, kHalf = 4, kWaves = 0;
 };
 
@@ -777,11 +786,15 @@ void count_workgroups(const DenseArgs &a, long long &n_vec, long long &tiles_v, 
     if (tiles_s > kMaxScalarGroups) tiles_s = kMaxScalarGroups;
 }
 
-template <typename IN, int OP, bool HAS_H, int STREAM, int NORMS>
-mlf_status launch(DenseArgs &a, hipStream_t stream, double *norms_out, size_t partials_capacity,
-                  double *update_norms_out)
+// Committed updates from which the streamed binary32 kernels use the shape for
+// MANY updates.
+constexpr int kManyUpdates = 16, kManyUpdatesAggregate = 20;
+
+template <typename IN, int OP, bool HAS_H, int STREAM, int NORMS, bool MANY>
+mlf_status launch_shape(DenseArgs &a, hipStream_t stream, double *norms_out, size_t partials_capacity,
+                        double *update_norms_out)
 {
-    typedef Shape<IN, STREAM != 0, NORMS> S;
+    typedef Shape<IN, STREAM != 0, NORMS, MANY> S;
     static_assert(S::kWaves == 0 || S::kWaves == 1, "the cap is one wavefront per SIMD, or none");
     static_assert(64 * S::kVpt * IN::kVec >= kMinTileElements || NORMS == kNoNorms, "a norms tile yields one partial pair");
     long long n_vec, tiles_v, tiles_s;
@@ -828,6 +841,20 @@ mlf_status launch(DenseArgs &a, hipStream_t stream, double *norms_out, size_t pa
         }
     }
     return MLF_OK;
+}
+
+template <typename IN, int OP, bool HAS_H, int STREAM, int NORMS>
+mlf_status launch(DenseArgs &a, hipStream_t stream, double *norms_out, size_t partials_capacity,
+                  double *update_norms_out)
+{
+    if constexpr (sizeof(typename IN::elem) == 4 && STREAM != 0) {
+        if (a.M >= (OP == kAggregate ? kManyUpdatesAggregate : kManyUpdates)) {
+            return launch_shape<IN, OP, HAS_H, STREAM, NORMS, true>(a, stream, norms_out, partials_capacity,
+                                                                    update_norms_out);
+        }
+    }
+    return launch_shape<IN, OP, HAS_H, STREAM, NORMS, false>(a, stream, norms_out, partials_capacity,
+                                                             update_norms_out);
 }
 
 template <typename IN, int OP, int STREAM, int NORMS>
