@@ -299,8 +299,8 @@ mlf_status mlf_divergence(const float *w_server, const float *w_replica, int64_t
  * mlf_divergence for callers that cannot allocate device memory and so have no
  * workspace to pass: code running under HIP graph capture, tight serving loops,
  * harnesses that forbid hipMalloc.  Same arguments without the workspace, same
- * kernels, same result bit for bit.  The partial sums go to an array of
- * (MLF_STATIC_MAX_N / 1024 + 4162) * 16 bytes (about 4.1 MiB) that is part of the
+ * kernels, same result bit for bit.  The partial sums go to an array of 12,352
+ * pairs of doubles (197,632 bytes) that is part of the
  * library's device code: every GPU the library runs on holds one copy until the
  * process ends.  The call allocates and frees nothing; the first call on a
  * device looks up the address of that device's copy (make it outside a graph

@@ -681,38 +681,45 @@ __global__ __launch_bounds__(kColumnThreads) void update_norms_finish_kernel(con
 // Exact server-replica divergence (Sec. 3.3 / 5.3: bounded consistency keeps
 // ||w_s - w_r||_2 below Div_max): squared distance of two binary32 vectors.
 // Same reduction scheme as the norms variants: one wavefront per workgroup, a
-// pair of partial sums per workgroup (the second stays 0), fixed order.
-constexpr int kDivUnroll = 4;       // 128-bit groups per lane and vector
+// pair of partial sums per workgroup (the second stays 0), fixed order.  The
+// first `groups_vec` workgroups take the tiles of the 128-bit region in turn
+// (tile, tile + groups_vec, ...): at most kDivMaxGroups of them, so that the
+// partial sums stay few enough for ONE reduction launch behind the kernel (a
+// second one costs 5 us, 6 % of this kernel on 61 M elements).
+constexpr int kDivUnroll = 4;               // 128-bit groups per lane, vector and tile
+constexpr long long kDivMaxGroups = 8192;   // workgroups of the 128-bit region
 
 __global__ __launch_bounds__(64) void divergence_kernel(const float *__restrict__ x,
                                                         const float *__restrict__ y, long long n,
                                                         long long n_vec, unsigned tiles_vec,
-                                                        double *partials)
+                                                        unsigned groups_vec, double *partials)
 {
     double sum = 0.0;
-    if (blockIdx.x < tiles_vec) {
+    if (blockIdx.x < groups_vec) {
         const long long groups = n_vec / 4;
-        const long long base = static_cast<long long>(blockIdx.x) * 64 * kDivUnroll + threadIdx.x;
-        f32x4 a[kDivUnroll], b[kDivUnroll];
+        for (unsigned tile = blockIdx.x; tile < tiles_vec; tile += groups_vec) {
+            const long long base = static_cast<long long>(tile) * 64 * kDivUnroll + threadIdx.x;
+            f32x4 a[kDivUnroll], b[kDivUnroll];
 #pragma unroll
-        for (int u = 0; u < kDivUnroll; ++u) {
-            const long long g = base + u * 64;
-            const bool ok = g < groups;
-            a[u] = ok ? __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(x) + g) : f32x4{0, 0, 0, 0};
-            b[u] = ok ? __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(y) + g) : f32x4{0, 0, 0, 0};
-        }
+            for (int u = 0; u < kDivUnroll; ++u) {
+                const long long g = base + u * 64;
+                const bool ok = g < groups;
+                a[u] = ok ? __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(x) + g) : f32x4{0, 0, 0, 0};
+                b[u] = ok ? __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(y) + g) : f32x4{0, 0, 0, 0};
+            }
 #pragma unroll
-        for (int u = 0; u < kDivUnroll; ++u) {
+            for (int u = 0; u < kDivUnroll; ++u) {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const double d = static_cast<double>(a[u][j]) - static_cast<double>(b[u][j]);
-                sum += d * d;
+                for (int j = 0; j < 4; ++j) {
+                    const double d = static_cast<double>(a[u][j]) - static_cast<double>(b[u][j]);
+                    sum += d * d;
+                }
             }
         }
     } else {
         const long long left = n - n_vec;
-        const long long stride = static_cast<long long>(gridDim.x - tiles_vec) * 64;
-        for (long long i = static_cast<long long>(blockIdx.x - tiles_vec) * 64 + threadIdx.x; i < left;
+        const long long stride = static_cast<long long>(gridDim.x - groups_vec) * 64;
+        for (long long i = static_cast<long long>(blockIdx.x - groups_vec) * 64 + threadIdx.x; i < left;
              i += stride) {
             const double d = static_cast<double>(x[n_vec + i]) - static_cast<double>(y[n_vec + i]);
             sum += d * d;
@@ -1049,10 +1056,11 @@ static constexpr size_t norms_partials_capacity(long long n)
     return static_cast<size_t>(n / kMinTileElements) + 2 + static_cast<size_t>(kMaxScalarGroups);
 }
 
-// The same for the divergence kernel alone (tiles of 64 * kDivUnroll groups).
-static constexpr size_t divergence_partials_capacity(long long n)
+// The same for the divergence kernel alone: its workgroups of the 128-bit
+// region are capped whatever n is.
+static constexpr size_t divergence_partials_capacity()
 {
-    return static_cast<size_t>(n / (64 * kDivUnroll * 4)) + 2 + static_cast<size_t>(kMaxScalarGroups);
+    return static_cast<size_t>(kDivMaxGroups) + static_cast<size_t>(kMaxScalarGroups);
 }
 
 extern "C" size_t mlf_norms_workspace_bytes(int64_t n)
@@ -1223,7 +1231,7 @@ extern "C" mlf_status mlf_divergence_bound(double h_norm_sq, const double *updat
 }
 
 // Squared distance of two vectors with the partial sums in `partials` (room for
-// capacity + kFinishSlices pairs, capacity >= divergence_partials_capacity(n)).
+// capacity + kFinishSlices pairs, capacity >= divergence_partials_capacity()).
 // Every partial that is read has been written by this call, so the buffer needs
 // no clearing.
 static mlf_status divergence_launch(const float *w_server, const float *w_replica, long long n,
@@ -1237,11 +1245,13 @@ static mlf_status divergence_launch(const float *w_server, const float *w_replic
     const long long tiles_v = (n_vec / 4 + per_tile - 1) / per_tile;
     long long tiles_s = (n - n_vec + 63) / 64;
     if (tiles_s > kMaxScalarGroups) tiles_s = kMaxScalarGroups;
-    if (static_cast<size_t>(tiles_v + tiles_s) > capacity) return MLF_EUNSUPPORTED;
-    const unsigned grid = static_cast<unsigned>(tiles_v + tiles_s);
+    if (tiles_v > 0xffffffffll) return MLF_EUNSUPPORTED;
+    const long long groups_v = tiles_v < kDivMaxGroups ? tiles_v : kDivMaxGroups;
+    if (static_cast<size_t>(groups_v + tiles_s) > capacity) return MLF_EUNSUPPORTED;
+    const unsigned grid = static_cast<unsigned>(groups_v + tiles_s);
     if (grid > 0) {
         if (!launch_kernel(divergence_kernel, dim3(grid), dim3(64), 0, s, w_server, w_replica, n, n_vec,
-                           static_cast<unsigned>(tiles_v), partials)) {
+                           static_cast<unsigned>(tiles_v), static_cast<unsigned>(groups_v), partials)) {
             return MLF_EHIP;
         }
     }
@@ -1280,7 +1290,7 @@ extern "C" mlf_status mlf_divergence(const float *w_server, const float *w_repli
 // name is only ever used in that lookup: host code passes the looked-up pointer.
 // ---------------------------------------------------------------------------
 constexpr size_t kStaticScratchBytes =
-    (divergence_partials_capacity(MLF_STATIC_MAX_N) + kFinishSlices) * 2 * sizeof(double);
+    (divergence_partials_capacity() + kFinishSlices) * 2 * sizeof(double);
 static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 constexpr int kMaxDevices = 64;
@@ -1316,7 +1326,7 @@ extern "C" mlf_status mlf_divergence_static(const float *w_server, const float *
     const mlf_status found = static_scratch(&partials);
     if (found != MLF_OK) return found;
     return divergence_launch(w_server, w_replica, n, dist_sq, partials,
-                             divergence_partials_capacity(MLF_STATIC_MAX_N), static_cast<hipStream_t>(stream));
+                             divergence_partials_capacity(), static_cast<hipStream_t>(stream));
 }
 
 extern "C" const char *mlf_status_string(mlf_status status)

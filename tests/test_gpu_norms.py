@@ -191,11 +191,12 @@ def test_replica_lags_then_catches_up():
     assert dist.item() > 0 and abs(dist.item() / swapped - 1) < 1e-2
 
 
-# ---- sizes whose partial sums are reduced in two stages (16,384 pairs and more) --------
+# ---- sizes above the small-input paths --------------------------------------------------
 
-def test_divergence_two_stage_reduction():
-    """17,000,005 elements: 16,602 partial pairs from the 128-bit region plus the
-    ragged tail's; the same path the benchmark times on 61 M elements."""
+def test_divergence_several_tiles_per_workgroup():
+    """17,000,005 elements: 16,602 tiles for the 8,192 workgroups of the 128-bit
+    region, so workgroups take two or three tiles each, plus the ragged tail; the
+    same path the benchmark times on 61 M elements."""
     n = 17_000_005
     g = torch.Generator(device="cuda")
     g.manual_seed(4242)
@@ -214,6 +215,7 @@ def test_divergence_two_stage_reduction():
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_aggregate_norm_two_stage_reduction(dtype):
+    # (partial sums are reduced in two launches from 16,384 pairs on)
     n = 17_000_005                                    # 33,204 partial pairs
     cfg = W.scaled(W.CONFIGS["cfg2"], n=n, K=3, dtype=dtype)
     d = W.dense_inputs(cfg, "cuda")

@@ -43,8 +43,8 @@ def _both(a, b, n):
 
 
 def test_two_calls_in_a_row_second_smaller():
-    # 17,000,005 elements: two-stage reduction of the partial sums, ragged tail;
-    # then 70,001 elements: single-stage reduction over a prefix of the same scratch.
+    # 17,000,005 elements: several tiles per workgroup, ragged tail; then 70,001
+    # elements: one tile per workgroup, partial sums over a prefix of the same scratch.
     for n, seed in ((17_000_005, 11), (70_001, 12), (3, 13), (1_050_000, 14)):
         a, b = _pair(n, seed)
         got, want = _both(a, b, n)
@@ -60,6 +60,18 @@ def test_unaligned_and_identical_vectors():
     assert got == want
     got, want = _both(a, a, 300_002)
     assert got == 0.0 and want == 0.0
+
+
+def test_largest_accepted_size():
+    """MLF_STATIC_MAX_N elements (2^28: 32 tiles per workgroup of the 128-bit region)."""
+    n = B.MLF_STATIC_MAX_N
+    a, b = _pair(n, 41)
+    got, want = _both(a, b, n)
+    assert got == want, (got, want)
+    ref = oracle.sum_sq_diff(W.to_host(a), W.to_host(b), threads=16)
+    assert abs(got - ref) <= 1e-12 * abs(ref), (got, ref)
+    del a, b
+    torch.cuda.empty_cache()
 
 
 def test_size_limit_and_errors():
