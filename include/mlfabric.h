@@ -175,10 +175,10 @@ mlf_status mlf_apply_grouped(float *model, float *momentum,
  * bits.  The order depends on n, on the data type of the updates, on whether
  * every pointer of the call is 16-byte aligned (128-bit or element-wise path),
  * on whether momentum is given, whether 4n bytes per written vector exceed
- * 256 MiB in total and, if so, whether 16 or more updates (20 or more for the
- * aggregate) are committed (these select the tile shape), and on the number of
- * XCDs of the device; calls that differ in any of these may differ in the last
- * bits.
+ * 256 MiB in total and, if so, whether 8 or more updates (4 or more for the
+ * aggregate, 16 or more for the update-norm variants below) are committed
+ * (these select the tile shape), and on the number of XCDs of the device; calls
+ * that differ in any of these may differ in the last bits.
  * The sums agree with the exactly rounded ones to about 1e-14 relative.
  *
  *   norm_sq / norms_sq  device, 1 / 2 doubles, 8-byte aligned; written
@@ -213,7 +213,8 @@ mlf_status mlf_apply_grouped_norms(float *model, float *momentum,
  * the commit sequence.  norm_sq / norms_sq are as in the calls above.  Sums in
  * binary64 in a fixed order (exact squares, rounded additions): repeatable bit
  * for bit for the same arguments on the same device; the order depends on what
- * the calls above list and on the number of compute units of the device, and a
+ * the calls above list and on the number of compute units of the device and
+ * the size of their LDS, and a
  * sum agrees with the exactly rounded one to about 1e-14 relative.  These
  * variants keep one running sum per update and lane on chip (binary64
  * arithmetic per update element) and walk the vector with a fixed number of

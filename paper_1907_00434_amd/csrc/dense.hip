@@ -117,50 +117,67 @@ struct BF16V4 {
 // Launch shapes.  A workgroup is one tile: THREADS lanes, each with VPT groups of
 // consecutive elements, THREADS groups apart.  The committed sequence is consumed
 // in blocks of HALF updates through two register buffers: the loads of the next
-// block are issued before the current one is consumed.  WAVES = 1 caps the
-// wavefronts per SIMD at one.  The values are the best of sweeps on MI355X:
+// block are issued before the current one is consumed.  A LIMITED shape is
+// launched with a bounded number of workgroups per compute unit, by reserving
+// that share of the unit's LDS for each (nothing is kept there); the number
+// depends on the length of the sequence, see limited_per_cu().  The values are
+// the best of sweeps on MI355X:
 //
 //  - binary32 updates, state streamed (more than the memory-side cache holds),
-//    MANY updates committed (16 or more; 20 or more for the plain aggregate):
-//    ONE wavefront per SIMD and the narrowest tile (one 128-bit group per lane,
-//    1 KiB per vector and wavefront).  The fewer and the narrower the tiles in
-//    flight, the shorter the stretch of every vector that the chip works on at
-//    one time, and the cheaper the write-back of model and momentum gets (an
-//    ordered apply of 32 updates of 61 M elements: 6.1-6.2 TB/s against 5.7-5.8
-//    with three wavefronts per SIMD and 2 KiB tiles; the same loads without the
-//    stores run at 7.1 TB/s either way).  Spreading the tiles in flight over 16
-//    distant regions costs 6 %; tiles of 512 bytes per vector lose 10-25 %;
-//  - the same with FEW updates: a single wavefront per SIMD then has too few
-//    loads in flight (an ordered apply of 1 to 6 updates ran at 3.2-4.4 TB/s
-//    in that shape), so the wide tile and the uncapped occupancy are used:
-//    6.2-6.5 TB/s from 1 to 8 updates; the shapes cross between 12 and 16;
+//    MANY updates committed (8 or more; 4 or more for the plain aggregate):
+//    the narrowest tile (one 128-bit group per lane, 1 KiB per vector and
+//    wavefront) and few one-wavefront workgroups per compute unit.  The fewer
+//    and the narrower the tiles in flight, the shorter the stretch of every
+//    vector that the chip works on at one time, and the cheaper the write-back
+//    of model and momentum gets: an ordered apply of 32 updates of 61 M
+//    elements runs at 0.773 of the peak with 4 per compute unit, 0.779 with 5,
+//    0.765 with 6, 0.756 with 7 or more, and at 0.72 with 2 KiB tiles; the same
+//    loads without the stores run at 0.89 either way.  With 4 (one per SIMD)
+//    the end of a tile - the stores, and for the norms variants the binary64
+//    squares, their reduction and the store of the pair - has nothing to hide
+//    behind: the grouped apply with norms runs at 0.736 with 4 and 0.773 with
+//    5.  Spreading the tiles in flight over 16 distant regions costs 6 %; tiles
+//    of 512 bytes per vector lose 10-25 %;
+//  - the same with FEW updates: the narrow tile then has too few loads in
+//    flight whatever the number of workgroups, so the wide tile and the
+//    unlimited occupancy are used (6.2-6.5 TB/s from 1 to 7 updates);
 //  - bfloat16 updates, state streamed: a quarter of the traffic is stores and
 //    64-bit update loads cover only 512 bytes per wavefront, so the wider tile
-//    and the uncapped occupancy are kept (6.4 TB/s; the narrow capped shape
-//    drops to 3.4 TB/s);
-//  - state that stays cached between calls: wider tiles, no cap.
+//    and the unlimited occupancy are kept (6.4 TB/s; the narrow shape at one
+//    wavefront per SIMD drops to 3.4 TB/s);
+//  - state that stays cached between calls: wider tiles, no limit.
+//
+// (The limit used to be set with the amdgpu_waves_per_eu attribute, one wavefront
+// per SIMD.  Under that attribute the compiler produced wrong code for other
+// instantiations of the tile template - a register that still held loaded data
+// was reused as a temporary - so it is no longer used anywhere.)
 template <typename IN, bool STREAMED, int NORMS, bool MANY>
 struct Shape;
 
 template <int NORMS>
 struct Shape<F32, true, NORMS, true> {      // streamed state, binary32, many updates
-    static constexpr int kThreads = 64, kVpt = 1, kHalf = 8, kWaves = 1;
+    static constexpr int kThreads = 64, kVpt = 1, kHalf = 8;
+    static constexpr bool kLimited = true;
 };
 template <int NORMS>
 struct Shape<F32, true, NORMS, false> {     // streamed state, binary32, few updates
-    static constexpr int kThreads = 64, kVpt = 2, kHalf = 8, kWaves = 0;
+    static constexpr int kThreads = 64, kVpt = 2, kHalf = 8;
+    static constexpr bool kLimited = false;
 };
 template <int NORMS, bool MANY>
 struct Shape<BF16V4, true, NORMS, MANY> {   // streamed state, bfloat16 updates
-    static constexpr int kThreads = 64, kVpt = 2, kHalf = 4, kWaves = 0;
+    static constexpr int kThreads = 64, kVpt = 2, kHalf = 4;
+    static constexpr bool kLimited = false;
 };
 template <int NORMS, bool MANY>
 struct Shape<F32, false, NORMS, MANY> {     // cached state, binary32 updates
-    static constexpr int kThreads = 64, kVpt = 2, kHalf = 8, kWaves = 0;
+    static constexpr int kThreads = 64, kVpt = 2, kHalf = 8;
+    static constexpr bool kLimited = false;
 };
 template <int NORMS, bool MANY>
 struct Shape<BF16V8, false, NORMS, MANY> {  // cached state, bfloat16 updates; with norms one wavefront per workgroup
-    static constexpr int kThreads = NORMS != 0 ? 64 : 256, kVpt = NORMS != 0 ? 2 : 1, kHalf = 4, kWaves = 0;
+    static constexpr int kThreads = NORMS != 0 ? 64 : 256, kVpt = NORMS != 0 ? 2 : 1, kHalf = 4;
+    static constexpr bool kLimited = false;
 };
 
 __device__ __forceinline__ float from_bits(uint32_t b) { return __uint_as_float(b); }
@@ -491,8 +508,7 @@ __device__ __forceinline__ long long xcd_tile(unsigned block, unsigned tiles, un
 // [n_vec, n): the ragged tail, or everything when a pointer of the call is not
 // 16-byte aligned.  Norms variants (one wavefront per workgroup) end with a
 // shuffle reduction in a fixed order and one pair of partial sums per workgroup.
-template <typename IN, int OP, bool HAS_H, int STREAM, int NORMS, int THREADS, int VPT, int HALF,
-          int WAVES>
+template <typename IN, int OP, bool HAS_H, int STREAM, int NORMS, int THREADS, int VPT, int HALF>
 __device__ __forceinline__ void dense_body(const DenseArgs &a)
 {
     static_assert(NORMS == kNoNorms || THREADS == 64, "norms are reduced within one wavefront");
@@ -551,20 +567,11 @@ __device__ __forceinline__ void dense_body(const DenseArgs &a)
     }
 }
 
-// The kernel proper.  WAVES > 0 caps the wavefronts per SIMD at WAVES (the
-// register allocation is raised to match, so the hardware cannot place more).
-template <typename IN, int OP, bool HAS_H, int STREAM, int NORMS, int THREADS, int VPT, int HALF,
-          int WAVES>
+// The kernel proper.
+template <typename IN, int OP, bool HAS_H, int STREAM, int NORMS, int THREADS, int VPT, int HALF>
 __global__ __launch_bounds__(THREADS) void dense_kernel(const DenseArgs a)
 {
-    dense_body<IN, OP, HAS_H, STREAM, NORMS, THREADS, VPT, HALF, WAVES>(a);
-}
-
-template <typename IN, int OP, bool HAS_H, int STREAM, int NORMS, int THREADS, int VPT, int HALF>
-__global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(1, 1)))
-void dense_kernel_one_wave(const DenseArgs a)
-{
-    dense_body<IN, OP, HAS_H, STREAM, NORMS, THREADS, VPT, HALF, 1>(a);
+    dense_body<IN, OP, HAS_H, STREAM, NORMS, THREADS, VPT, HALF>(a);
 }
 
 // Sums pairs of partial sums in a fixed order, so that the norms of a call are
@@ -781,6 +788,29 @@ unsigned cu_count()
     return static_cast<unsigned>(n);
 }
 
+// LDS of a compute unit of the current device, looked up once per device
+// (gfx950: 160 KiB), and the unit it is handed out in (1,280 bytes there: a
+// request is rounded up to it, measured through the occupancy it leaves).
+constexpr size_t kLdsGranule = 1280;
+
+size_t lds_per_cu()
+{
+    constexpr int kMaxDevices = 64;
+    constexpr int kDefault = 160 * 1024;
+    static std::atomic<int> cached[kMaxDevices];
+    int device = 0;
+    if (hipGetDevice(&device) != hipSuccess || device < 0 || device >= kMaxDevices) return kDefault;
+    int n = cached[device].load(std::memory_order_relaxed);
+    if (n == 0) {
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMaxSharedMemoryPerMultiprocessor, device) != hipSuccess ||
+            n < 65536) {
+            n = kDefault;
+        }
+        cached[device].store(n, std::memory_order_relaxed);
+    }
+    return static_cast<size_t>(n);
+}
+
 // Workgroups a launch of this shape uses (tiles of the 128-bit region plus the
 // workgroups of the element-wise region).
 template <typename IN, int THREADS, int VPT>
@@ -793,29 +823,62 @@ void count_workgroups(const DenseArgs &a, long long &n_vec, long long &tiles_v, 
     if (tiles_s > kMaxScalarGroups) tiles_s = kMaxScalarGroups;
 }
 
-// Committed updates from which the streamed binary32 kernels use the shape for
-// MANY updates.
-constexpr int kManyUpdates = 16, kManyUpdatesAggregate = 20;
+// Committed updates from which the streamed binary32 kernels use the narrow shape
+// (MANY), and the workgroups per compute unit that shape is limited to.  Measured
+// on 61 M elements (TB/s, wide shape | narrow shape limited to 4, 5, 6, 8, 12):
+//   ordered apply  M = 6: 6.38 | 4.12 4.82 5.43 6.31 6.32     aggregate  M = 6: 6.36 | 4.01 4.68 5.27 5.79 6.74
+//                  M = 8: 6.23 | 6.40 6.74 6.69 6.62 6.60                M = 8: 6.25 | 5.69 6.22 6.58 6.54 6.48
+//                  M = 13: 6.18 | 5.58 6.20 6.58 6.63 6.62               M = 13: 6.09 | 5.06 5.69 6.20 6.71 6.48
+//                  M = 16: 6.11 | 6.36 6.46 6.34 6.37 6.36               M = 16: 6.11 | 6.22 6.65 6.55 6.47 6.30
+//                  M = 18: 6.04 | 5.93 6.36 6.44 6.36 6.36               M = 18: 6.03 | 5.84 6.39 6.61 6.43 6.30
+//                  M = 32: 5.84 | 6.26 6.24 6.13 6.02 6.04               M = 32: 6.12 | 6.63 6.55 6.44 6.32 6.17
+// The longer the sequence, the fewer workgroups should be in flight; a sequence
+// that is a whole number of blocks wants fewer than its neighbours, whose
+// remainder pieces are loaded only once the last whole block has been consumed.
+//
+// The update-norm variants walk the tiles with as many workgroups as are
+// resident, and do best with the narrow shape from 16 updates on and one
+// workgroup per SIMD (32 updates of 61 M elements: 0.70 of the peak with 4 per
+// compute unit, 0.66 with 5, 0.65 with 6 or 8).
+constexpr int kManyUpdates = 8, kManyUpdatesAggregate = 4, kManyUpdatesUpdateNorms = 16;
+
+template <int NORMS>
+inline unsigned limited_per_cu(int M)
+{
+    if (NORMS == kUpdateNorms) return 4;
+    if (M < 8) return 12;               // (the plain aggregate only: as many as fit, about)
+    if (M % 8 == 0 || M >= 24) return 5;
+    return M >= 16 ? 6 : 8;
+}
 
 template <typename IN, int OP, bool HAS_H, int STREAM, int NORMS, bool MANY>
 mlf_status launch_shape(DenseArgs &a, hipStream_t stream, double *norms_out, size_t partials_capacity,
                         double *update_norms_out)
 {
     typedef Shape<IN, STREAM != 0, NORMS, MANY> S;
-    static_assert(S::kWaves == 0 || S::kWaves == 1, "the cap is one wavefront per SIMD, or none");
+    static_assert(!S::kLimited || S::kThreads == 64, "the limit counts one-wavefront workgroups");
     static_assert(64 * S::kVpt * IN::kVec >= kMinTileElements || NORMS == kNoNorms, "a norms tile yields one partial pair");
     long long n_vec, tiles_v, tiles_s;
     count_workgroups<IN, S::kThreads, S::kVpt>(a, n_vec, tiles_v, tiles_s);
     if (tiles_v > 0xffffffffll) return MLF_EUNSUPPORTED;
     long long groups_v = tiles_v;
+    // Dynamic LDS of a workgroup: the running sums of the update-norm variants,
+    // and for a shape that limits the workgroups per compute unit at least that
+    // share of the unit's LDS.
     size_t lds = 0;
+    if constexpr (NORMS == kUpdateNorms) lds = static_cast<size_t>(a.M) * S::kThreads * sizeof(double);
+    long long per_cu = 12;      // one-wavefront workgroups a compute unit holds when nothing limits them, about
+    if constexpr (S::kLimited) {
+        const size_t all = lds_per_cu();
+        const size_t share = all / limited_per_cu<NORMS>(a.M) / kLdsGranule * kLdsGranule;
+        if (lds < share) lds = share;
+        per_cu = static_cast<long long>(all / ((lds + kLdsGranule - 1) / kLdsGranule * kLdsGranule));
+    }
     if constexpr (NORMS == kUpdateNorms) {
-        // As many workgroups (of one wavefront) as the device keeps resident:
-        // one per SIMD where the shape caps it at that, a few otherwise.
-        const long long resident = static_cast<long long>(cu_count()) * 4 * (S::kWaves == 1 ? 1 : 3);
+        // As many workgroups (of one wavefront) as the device keeps resident.
+        const long long resident = static_cast<long long>(cu_count()) * per_cu;
         const long long cap = resident < 1 ? 1024 : resident > kUpdateNormMaxGroups ? kUpdateNormMaxGroups : resident;
         if (groups_v > cap) groups_v = cap;
-        lds = static_cast<size_t>(a.M) * S::kThreads * sizeof(double);
     }
     if (groups_v + tiles_s > 0x7fffffffll) return MLF_EUNSUPPORTED;
     if (NORMS != kNoNorms && static_cast<size_t>(groups_v + tiles_s) > partials_capacity) return MLF_EINVAL;
@@ -825,14 +888,8 @@ mlf_status launch_shape(DenseArgs &a, hipStream_t stream, double *norms_out, siz
     a.xcds = xcd_count();
     const unsigned grid = static_cast<unsigned>(groups_v + tiles_s);
     if (grid > 0) {
-        bool ok;
-        if constexpr (S::kWaves == 1) {
-            ok = launch_kernel(dense_kernel_one_wave<IN, OP, HAS_H, STREAM, NORMS, S::kThreads, S::kVpt, S::kHalf>,
-                               dim3(grid), dim3(S::kThreads), lds, stream, a);
-        } else {
-            ok = launch_kernel(dense_kernel<IN, OP, HAS_H, STREAM, NORMS, S::kThreads, S::kVpt, S::kHalf, 0>,
-                               dim3(grid), dim3(S::kThreads), lds, stream, a);
-        }
+        const bool ok = launch_kernel(dense_kernel<IN, OP, HAS_H, STREAM, NORMS, S::kThreads, S::kVpt, S::kHalf>,
+                                      dim3(grid), dim3(S::kThreads), lds, stream, a);
         if (!ok) return MLF_EHIP;
     }
     if constexpr (NORMS == kCallNorms) {
@@ -855,7 +912,7 @@ mlf_status launch(DenseArgs &a, hipStream_t stream, double *norms_out, size_t pa
                   double *update_norms_out)
 {
     if constexpr (sizeof(typename IN::elem) == 4 && STREAM != 0) {
-        if (a.M >= (OP == kAggregate ? kManyUpdatesAggregate : kManyUpdates)) {
+        if (a.M >= (NORMS == kUpdateNorms ? kManyUpdatesUpdateNorms : OP == kAggregate ? kManyUpdatesAggregate : kManyUpdates)) {
             return launch_shape<IN, OP, HAS_H, STREAM, NORMS, true>(a, stream, norms_out, partials_capacity,
                                                                     update_norms_out);
         }

@@ -32,10 +32,11 @@ PROFILES = os.path.join(ROOT, "profiles")
 KERNEL_SOURCES = ["paper_1907_00434_amd/csrc/dense.hip", "paper_1907_00434_amd/csrc/sparse.hip"]
 SPARSE_KERNELS = ("clear_kernel", "sample_kernel", "plan_kernel", "coarse_partition_kernel",
                   "fine_partition_kernel", "accumulate_kernel")
-KEY = ("Kernel name key: `dense_kernel[_one_wave]<IN, OP, HAS_H, STREAM, NORMS, THREADS, VPT, HALF>`; OP 0 = aggregate, "
+KEY = ("Kernel name key: `dense_kernel<IN, OP, HAS_H, STREAM, NORMS, THREADS, VPT, HALF>`; OP 0 = aggregate, "
        "1 = aggregate+apply, 2 = ordered apply, 3 = grouped apply; STREAM 3 = model / momentum (or the aggregate's "
        "output) accessed with the no-reuse hint; NORMS 1 = the call's squared norms reduced in the same pass, "
-       "2 = those and one per update; `_one_wave` = capped at one wavefront per SIMD.")
+       "2 = those and one per update; THREADS x VPT 64 x 1 = the shape for many updates on streamed state, launched "
+       "with five workgroups per compute unit.")
 
 
 def kernel_source_digest():
@@ -66,7 +67,7 @@ def find(directory, suffix):
 def dense_workload(kernel):
     """(label, algorithmic bytes) of the dense kernels profile_workloads / bench.py launch."""
     import workloads as W
-    m = re.match(r"dense_kernel(_one_wave)?<(\w+), (\d), (true|false), (\d), (\d),", kernel)
+    m = re.match(r"dense_kernel()<(\w+), (\d), (true|false), (\d), (\d),", kernel)
     if not m:
         if kernel.startswith("divergence_kernel"):
             return "cfg3: exact divergence of two 61,100,840-element models", 8 * W.CONFIGS["cfg3"].n
