@@ -67,7 +67,7 @@ def find(directory, suffix):
 def dense_workload(kernel):
     """(label, algorithmic bytes) of the dense kernels profile_workloads / bench.py launch."""
     import workloads as W
-    m = re.match(r"dense_kernel()<(\w+), (\d), (true|false), (\d), (\d),", kernel)
+    m = re.match(r"dense_kernel()<(\w+), (\d), (true|false), (\d), (\d), (\d+), (\d+),", kernel)
     if not m:
         if kernel.startswith("divergence_kernel"):
             return "cfg3: exact divergence of two 61,100,840-element models", 8 * W.CONFIGS["cfg3"].n
@@ -75,6 +75,10 @@ def dense_workload(kernel):
             return "cfg5 shape: 8 dense int32 delta matrices 100,000 x 1,000 (nominal bytes)", 40 * 100_000 * 1_000
         return "", None
     kind, op, has_h, stream, norms = m.group(2), int(m.group(3)), m.group(4) == "true", int(m.group(5)), int(m.group(6))
+    if kind == "F32" and op == 0 and norms == 0 and int(m.group(8)) == 2:
+        # the only plain binary32 aggregate of few updates these programs launch (the wide tile)
+        return ("cfg4-sized vectors: aggregate of 3 binary32 updates (traffic-mix reference)",
+                16 * W.CONFIGS["cfg4"].n)
     call = ["aggregate", "aggregate+apply", "ordered apply", "grouped apply"][op]
     call += ["", " + norms", " + norms of every update"][norms]
     if kind.startswith("BF16"):

@@ -5,14 +5,16 @@ bit for bit.
 Why every length: the kernels consume the sequence in double-buffered blocks of
 8 updates and a halving remainder (4, 2, 1), so the code a launch runs through
 is chosen by the parity of the number of whole blocks and by the three bits of
-the remainder; from 16 (20 for the plain aggregate) committed updates on, the
-binary32 kernels also change to their one-wavefront-per-SIMD launch shape, which
-is a separate set of instantiations.  16 .. 31 covers every combination of block
-parity and remainder in that shape, 32 .. 40 repeats the loop, 1 .. 15 does the
-same for the shape used with few updates.  The compiler has produced wrong code
-for other instantiations of this template under the one-wavefront cap (a register
-still holding loaded data reused as a temporary), always on every tile of the
-launch: a test per path is what guards the instantiations that ship.
+the remainder; from 8 (4 for the plain aggregate, 16 for the update-norm
+variants) committed updates on, the binary32 kernels also change to their narrow
+launch shape, which is a separate set of instantiations, and the number of
+workgroups per compute unit they are launched with changes at 8, 9, 16, 17 and
+24.  16 .. 31 covers every combination of block parity and remainder, 32 .. 40
+repeats the loop, 1 .. 15 does the same across the change of shape.  The
+compiler has produced wrong code for other instantiations of this template (a
+register still holding loaded data reused as a temporary, under an occupancy
+attribute the library no longer uses), always on every tile of the launch: a
+test per path is what guards the instantiations that ship.
 
 The norms variants share the data path: their model / momentum / output must be
 the same bits, their norms within 1e-12 of the oracle's exactly rounded sums."""

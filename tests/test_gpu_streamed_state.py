@@ -1,11 +1,11 @@
 """GPU parity of the dense calls on vectors large enough that model and momentum
 are streamed (more than 256 MiB of state), with sequence lengths that are not
 multiples of the number of updates loaded together: 17, 31, 33 and 64 take every
-branch of the halving remainder, for binary32 and bfloat16 updates; 1, 3, 8 and
-15 take the launch shape for few updates, and 15 / 16 and 19 / 20 lie on either
-side of where the binary32 kernels change shape (16 committed updates, 20 for
-the plain aggregate).  Every output element is compared with the oracle bit for
-bit.
+branch of the halving remainder, for binary32 and bfloat16 updates; 1, 3 and 7
+take the launch shape for few updates, and 3 / 4 and 7 / 8 lie on either side of
+where the binary32 kernels change shape (8 committed updates, 4 for the plain
+aggregate); 15 / 16 and 23 / 24 are where the number of workgroups per compute
+unit changes.  Every output element is compared with the oracle bit for bit.
 
 One set of 64 update vectors per data type serves all sequence lengths (the
 order lists a prefix of a seeded permutation)."""
@@ -21,7 +21,7 @@ from parity import assert_same_bits
 pytestmark = pytest.mark.gpu
 
 N = 33_554_432 + 1_005          # model + momentum = 256 MiB + 8 KB: streamed; ragged tail of 5 / 1
-LENGTHS = [1, 3, 8, 15, 16, 17, 19, 20, 31, 33, 64]
+LENGTHS = [1, 3, 4, 7, 8, 15, 16, 17, 23, 24, 31, 33, 64]
 THREADS = 16
 
 

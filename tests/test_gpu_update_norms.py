@@ -108,7 +108,7 @@ def test_apply_grouped_update_norms_and_the_bound(dtype, n, K):
 
 
 def test_streamed_state_and_the_full_batch_of_32_updates():
-    """Model + momentum above 256 MiB (the streamed, one-wavefront-per-SIMD
+    """Model + momentum above 256 MiB (the streamed, narrow launch
     shape), 32 committed updates: 8 forwarded directly, three groups of 8."""
     n = 36_000_003
     cfg = W.scaled(W.CONFIGS["cfg3"], n=n)
