@@ -772,22 +772,6 @@ unsigned xcd_count()
     return static_cast<unsigned>(n);
 }
 
-// Compute units of the current device, looked up once per device (0 when the
-// runtime cannot tell).
-unsigned cu_count()
-{
-    constexpr int kMaxDevices = 64;
-    static std::atomic<int> cached[kMaxDevices];
-    int device = 0;
-    if (hipGetDevice(&device) != hipSuccess || device < 0 || device >= kMaxDevices) return 0;
-    int n = cached[device].load(std::memory_order_relaxed);
-    if (n == 0) {
-        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess || n < 1) return 0;
-        cached[device].store(n, std::memory_order_relaxed);
-    }
-    return static_cast<unsigned>(n);
-}
-
 // LDS of a compute unit of the current device, looked up once per device
 // (gfx950: 160 KiB), and the unit it is handed out in (1,280 bytes there: a
 // request is rounded up to it, measured through the occupancy it leaves).

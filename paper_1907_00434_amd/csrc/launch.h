@@ -1,4 +1,4 @@
-// Kernel launch helper shared by the kernel sources of the library.
+// Kernel launch helper and device queries shared by the kernel sources of the library.
 #ifndef MLF_LAUNCH_H
 #define MLF_LAUNCH_H
 
@@ -6,6 +6,7 @@
 
 #include <stddef.h>
 
+#include <atomic>
 #include <tuple>
 #include <utility>
 
@@ -33,6 +34,22 @@ bool launch_kernel(void (*kernel)(PARAMS...), dim3 grid, dim3 block, size_t lds,
     std::tuple<PARAMS...> values{static_cast<PARAMS>(args)...};
     return mlf_detail::launch_with(kernel, grid, block, lds, stream, values,
                                    std::index_sequence_for<PARAMS...>{});
+}
+
+// Compute units of the current device, looked up once per device (0 when the
+// runtime cannot tell).
+inline unsigned cu_count()
+{
+    constexpr int kMaxDevices = 64;
+    static std::atomic<int> cached[kMaxDevices];
+    int device = 0;
+    if (hipGetDevice(&device) != hipSuccess || device < 0 || device >= kMaxDevices) return 0;
+    int n = cached[device].load(std::memory_order_relaxed);
+    if (n == 0) {
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess || n < 1) return 0;
+        cached[device].store(n, std::memory_order_relaxed);
+    }
+    return static_cast<unsigned>(n);
 }
 
 #endif  // MLF_LAUNCH_H

@@ -926,7 +926,7 @@ __global__ __launch_bounds__(kPartThreads) void fine_partition_kernel(int32_t *c
     for (int i = 0; i < kPartItems; ++i) {
         const uint32_t r = begin + i * kPartThreads + threadIdx.x;
         live[i] = r < end;
-        word[i] = plan.tmp[min(r, end - 1)];                  // (no branch around the load)
+        word[i] = __builtin_nontemporal_load(&plan.tmp[min(r, end - 1)]);      // (no branch around the load)
         dig[i] = live[i] ? (word[i] >> kTileBits) & (kFinePerCoarse - 1) : 0u;
     }
     partition_step(
@@ -950,7 +950,10 @@ constexpr int kAccUnroll = 4;       // 128-bit record loads in flight per lane
 // Adds the records [begin, end) of one tile into its LDS image.  The records
 // are read with 128-bit loads (4 records each), kAccUnroll of them in flight per
 // lane; the few records before the first and after the last aligned group go
-// one by one.
+// one by one.  Records are read once, here and by the fine level: their loads
+// carry the no-reuse hint (-2 % on the whole call with word id = rank - 1, -8 %
+// with permuted ids).  Their STORES must not: the runs a step writes start and
+// end inside lines, and it is the cache that puts the pieces together (+25 %).
 __device__ __forceinline__ void accumulate_records(int32_t *image, const uint32_t *__restrict__ sorted,
                                                    uint32_t begin, uint32_t end)
 {
@@ -958,7 +961,7 @@ __device__ __forceinline__ void accumulate_records(int32_t *image, const uint32_
     const uint32_t first = min((begin + 3) / 4 * 4, end);
     const uint32_t last = max(first, end / 4 * 4);
     auto add_one = [&](uint32_t r) {
-        const uint32_t v = sorted[r];
+        const uint32_t v = __builtin_nontemporal_load(&sorted[r]);
         lds_add(&image[v & (kTileCells - 1)], record_delta(v));
     };
     if (threadIdx.x < first - begin) add_one(begin + threadIdx.x);
@@ -971,7 +974,7 @@ __device__ __forceinline__ void accumulate_records(int32_t *image, const uint32_
 #pragma unroll
         for (int u = 0; u < kAccUnroll; ++u) {
             const uint32_t g = g0 + u * kAccThreads;
-            x[u] = g < g_end ? groups[g] : u32x4{0, 0, 0, 0};
+            x[u] = g < g_end ? __builtin_nontemporal_load(&groups[g]) : u32x4{0, 0, 0, 0};
         }
 #pragma unroll
         for (int u = 0; u < kAccUnroll; ++u) {
@@ -1030,7 +1033,12 @@ __global__ __launch_bounds__(kAccThreads) void accumulate_kernel(int32_t *__rest
     if (chunks == 1) {
         // This workgroup is the only writer of the tile: plain read-modify-write
         // (int32 addition wraps; done on unsigned values).  All loads of a lane
-        // are issued before its first store, so their latencies overlap.
+        // are issued before its first store, so their latencies overlap.  A
+        // 128-byte stretch (8 lanes) is written whole as soon as one of its
+        // groups has changed, and counts is read and written with the no-reuse
+        // hint: lines written in pieces cost the memory a read-modify-write,
+        // and the matrix is far larger than any cache (both together: -13 % on
+        // the whole call for 64 M LDA triples; either alone: -5 % and 0).
         u32x4 *dst4 = reinterpret_cast<u32x4 *>(dst);
         u32x4 add[kGroupsPerLane], old[kGroupsPerLane];
         bool touch[kGroupsPerLane];
@@ -1038,12 +1046,14 @@ __global__ __launch_bounds__(kAccThreads) void accumulate_kernel(int32_t *__rest
         for (int k = 0; k < kGroupsPerLane; ++k) {
             const uint32_t i = k * kAccThreads + threadIdx.x;
             add[k] = __builtin_bit_cast(u32x4, image4[i]);
-            touch[k] = i < groups && (add[k].x | add[k].y | add[k].z | add[k].w) != 0;
-            old[k] = touch[k] ? dst4[i] : u32x4{0, 0, 0, 0};
+            const bool changed = i < groups && (add[k].x | add[k].y | add[k].z | add[k].w) != 0;
+            const unsigned long long changed_lanes = __ballot(changed);
+            touch[k] = i < groups && ((changed_lanes >> (threadIdx.x & 56)) & 0xffull) != 0;
+            old[k] = touch[k] ? __builtin_nontemporal_load(&dst4[i]) : u32x4{0, 0, 0, 0};
         }
 #pragma unroll
         for (int k = 0; k < kGroupsPerLane; ++k) {
-            if (touch[k]) dst4[k * kAccThreads + threadIdx.x] = old[k] + add[k];
+            if (touch[k]) __builtin_nontemporal_store(old[k] + add[k], &dst4[k * kAccThreads + threadIdx.x]);
         }
         for (uint32_t i = groups * 4 + threadIdx.x; i < cells; i += kAccThreads) {
             const int32_t v = image[i];
@@ -1065,11 +1075,43 @@ __global__ __launch_bounds__(kAccThreads) void accumulate_kernel(int32_t *__rest
 // with 128-bit loads, counts is read and written once, each cell is owned by
 // one lane (no atomics on counts); the column sums go through the per-workgroup
 // LDS copy of the totals.
+//
+// Two shapes, chosen by whether counts fits the memory-side cache (STREAM):
+//  - larger (measured on 8 matrices of 100,000 x 1,000, fraction of 8 TB/s on
+//    (4K + 8) bytes per cell): one-wavefront workgroups that walk 1 KiB tiles,
+//    four to twelve per compute unit, every group of counts written back whether or not
+//    its sum is zero, counts accessed with the no-reuse hint: 0.74.  Writing
+//    back only the groups whose sum is not zero saves a quarter of the written
+//    bytes and costs 8 %: what reaches memory are then lines written in pieces.
+//    With 1,024-lane workgroups (two per compute unit) the same kernel runs at
+//    0.67, with the conditional write-back and plain accesses at 0.63; 2 or 4
+//    groups per lane: 0.66-0.71;
+//  - smaller: 1,024-lane workgroups, two groups per lane, up to 2,048 of them,
+//    plain accesses, groups with a zero sum not written (the lines stay in the
+//    cache, where pieces merge): a 10,000 x 1,000 matrix takes 74 us against
+//    85 us in the other shape, 1,000 x 1,000 10 us against 19 us.
 // ---------------------------------------------------------------------------
 constexpr int kDeltaChunk = 8;              // delta matrices whose loads are in flight together
-constexpr int kDeltaVpt = 2;                // 128-bit groups per lane and step
-constexpr int kDeltaThreads = 1024;         // lanes of a workgroup
-constexpr unsigned kDeltaMaxGrid = 2048;    // workgroups of the persistent grid
+constexpr unsigned kDeltaMaxGrid = 2048;    // otherwise: workgroups of the persistent grid
+constexpr unsigned long long kDeltaCachedBytes = 256ull << 20;     // counts up to this size are left cacheable
+
+// STREAM: workgroups of the persistent grid per compute unit, by the number of
+// delta matrices (100,000 x 1,000 cells; fraction of 8 TB/s with 4, 6, 8, 12 per
+// unit: K = 1: 0.41 0.54 0.62 0.64; K = 2: 0.50 0.65 0.71 0.69; K = 4: 0.64 0.76
+// 0.74 0.71; K = 8: 0.74 0.72 0.72 0.67; K = 12: 0.68 0.71 0.72 0.67; K = 16:
+// 0.72 0.71 0.71 0.67; K = 32: 0.70 0.71 0.71 0.68).
+inline unsigned delta_per_cu(int K)
+{
+    if (K == 1) return 12;
+    if (K <= 3) return 8;
+    return K == 8 || K == 16 ? 4 : 6;
+}
+
+template <bool STREAM>
+struct DeltaShape {
+    static constexpr int kThreads = STREAM ? 64 : 1024;     // lanes of a workgroup
+    static constexpr int kVpt = STREAM ? 1 : 2;             // 128-bit groups per lane and step
+};
 
 struct DeltaArgs {
     const int32_t *delta[MLF_MAX_K];
@@ -1093,9 +1135,10 @@ __device__ __forceinline__ void add_to_total(const DeltaArgs &a, int32_t *lds_to
     }
 }
 
-template <bool LDS_TOTALS>
-__global__ __launch_bounds__(kDeltaThreads) void dense_delta_kernel(const DeltaArgs a)
+template <bool LDS_TOTALS, bool STREAM>
+__global__ __launch_bounds__(DeltaShape<STREAM>::kThreads) void dense_delta_kernel(const DeltaArgs a)
 {
+    constexpr int kDeltaThreads = DeltaShape<STREAM>::kThreads, kDeltaVpt = DeltaShape<STREAM>::kVpt;
     typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
     extern __shared__ int32_t lds_totals[];
     const uint32_t T = static_cast<uint32_t>(a.T);
@@ -1108,8 +1151,8 @@ __global__ __launch_bounds__(kDeltaThreads) void dense_delta_kernel(const DeltaA
 
     // 128-bit region: groups of 4 consecutive cells, kDeltaVpt groups per lane
     // and step, kDeltaThreads groups apart.  The counts are loaded together with the
-    // deltas (not after their sum is known), so that the latencies overlap; a
-    // group whose summed delta is zero is not written back.
+    // deltas (not after their sum is known), so that the latencies overlap.
+    // STREAM: every group is written back, so that whole lines reach the memory.
     const unsigned long long groups = a.n_vec / 4;
     u32x4 *counts4 = reinterpret_cast<u32x4 *>(a.counts);
     for (unsigned long long g0 = first + static_cast<unsigned long long>(blockIdx.x) * kDeltaThreads * (kDeltaVpt - 1);
@@ -1121,7 +1164,7 @@ __global__ __launch_bounds__(kDeltaThreads) void dense_delta_kernel(const DeltaA
             const unsigned long long g = g0 + static_cast<unsigned long long>(v) * kDeltaThreads;
             on[v] = g < groups;
             sum[v] = u32x4{0, 0, 0, 0};
-            old[v] = on[v] ? counts4[g] : u32x4{0, 0, 0, 0};
+            old[v] = !on[v] ? u32x4{0, 0, 0, 0} : STREAM ? __builtin_nontemporal_load(&counts4[g]) : counts4[g];
         }
         for (int k0 = 0; k0 < a.K; k0 += kDeltaChunk) {
             u32x4 x[kDeltaChunk][kDeltaVpt];
@@ -1145,9 +1188,15 @@ __global__ __launch_bounds__(kDeltaThreads) void dense_delta_kernel(const DeltaA
         }
 #pragma unroll
         for (int v = 0; v < kDeltaVpt; ++v) {
-            if (on[v] && (sum[v].x | sum[v].y | sum[v].z | sum[v].w) != 0) {
-                const unsigned long long g = g0 + static_cast<unsigned long long>(v) * kDeltaThreads;
-                counts4[g] = old[v] + sum[v];
+            if (!on[v]) continue;
+            const unsigned long long g = g0 + static_cast<unsigned long long>(v) * kDeltaThreads;
+            const bool changed = (sum[v].x | sum[v].y | sum[v].z | sum[v].w) != 0;
+            if constexpr (STREAM) {
+                __builtin_nontemporal_store(old[v] + sum[v], &counts4[g]);
+            } else {
+                if (changed) counts4[g] = old[v] + sum[v];
+            }
+            if (changed) {
                 uint32_t col = static_cast<uint32_t>((g * 4) % T);
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
@@ -1428,14 +1477,22 @@ extern "C" mlf_status mlf_counts_add_dense(int32_t *counts, int32_t *totals, int
     a.K = K;
     a.T = T;
     const unsigned long long work = a.n_vec / 4 > a.n_cells - a.n_vec ? a.n_vec / 4 : a.n_cells - a.n_vec;
-    unsigned long long tiles = (work + kDeltaThreads * kDeltaVpt - 1) / (kDeltaThreads * kDeltaVpt);
-    if (tiles > kDeltaMaxGrid) tiles = kDeltaMaxGrid;
-    if (tiles < 1) tiles = 1;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const bool ok = totals != nullptr && T <= kMaxLdsTopics
-                        ? launch_kernel(dense_delta_kernel<true>, dim3(static_cast<unsigned>(tiles)),
-                                        dim3(kDeltaThreads), static_cast<size_t>(T) * sizeof(int32_t), s, a)
-                        : launch_kernel(dense_delta_kernel<false>, dim3(static_cast<unsigned>(tiles)),
-                                        dim3(kDeltaThreads), 0, s, a);
+    const bool lds_totals = totals != nullptr && T <= kMaxLdsTopics;
+    const bool streamed = bytes > kDeltaCachedBytes;
+    const unsigned threads = streamed ? DeltaShape<true>::kThreads : DeltaShape<false>::kThreads;
+    const unsigned per_step = threads * (streamed ? DeltaShape<true>::kVpt : DeltaShape<false>::kVpt);
+    unsigned long long tiles = (work + per_step - 1) / per_step;
+    const unsigned cus = cu_count();
+    const unsigned long long grid_max =
+        streamed ? static_cast<unsigned long long>(cus > 0 ? cus : 256) * delta_per_cu(K) : kDeltaMaxGrid;
+    if (tiles > grid_max) tiles = grid_max;
+    if (tiles < 1) tiles = 1;
+    const dim3 grid(static_cast<unsigned>(tiles)), block(threads);
+    const size_t lds = lds_totals ? static_cast<size_t>(T) * sizeof(int32_t) : 0;
+    const bool ok = lds_totals ? (streamed ? launch_kernel(dense_delta_kernel<true, true>, grid, block, lds, s, a)
+                                           : launch_kernel(dense_delta_kernel<true, false>, grid, block, lds, s, a))
+                               : (streamed ? launch_kernel(dense_delta_kernel<false, true>, grid, block, lds, s, a)
+                                           : launch_kernel(dense_delta_kernel<false, false>, grid, block, lds, s, a));
     return ok ? MLF_OK : MLF_EHIP;
 }
