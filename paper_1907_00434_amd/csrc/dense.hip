@@ -150,7 +150,7 @@ struct BF16V4 {
 // (The limit used to be set with the amdgpu_waves_per_eu attribute, one wavefront
 // per SIMD.  Under that attribute the compiler produced wrong code for other
 // instantiations of the tile template - a register that still held loaded data
-// was reused as a temporary - so it is no longer used anywhere.)
+// was reused as a temporary - so the dense kernels no longer use it.)
 template <typename IN, bool STREAMED, int NORMS, bool MANY>
 struct Shape;
 
