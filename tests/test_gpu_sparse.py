@@ -254,6 +254,32 @@ def test_dense_delta_full_matrix_size():
     torch.cuda.empty_cache()
 
 
+@pytest.mark.parametrize("V,T,K", [(8193, 8192, 1), (8193, 8192, 3), (8193, 8192, 9), (16389, 4099, 17),
+                                   (3400, 20_000, 2)])
+def test_dense_delta_matrix_larger_than_the_cache(V, T, K):
+    """More than 256 MiB of counts: the kernel takes its other shape (one-wavefront
+    workgroups, every group written back, no-reuse hints), with one and with
+    several blocks of 8 matrices, totals in LDS and (20,000 topics) in memory,
+    a cell count that is not a multiple of 4, non-zero counts to start from."""
+    assert 4 * V * T > 256 << 20
+    g = torch.Generator(device="cuda")
+    g.manual_seed(V + T + K)
+    counts = torch.randint(-50, 50, (V * T,), generator=g, device="cuda", dtype=torch.int32)
+    totals = torch.randint(0, 1000, (T,), generator=g, device="cuda", dtype=torch.int32)
+    run_dense_delta(V, T, delta_matrices(V, T, K, seed=K, density=0.03), counts, totals)
+    torch.cuda.empty_cache()
+
+
+def test_dense_delta_larger_than_the_cache_misaligned_and_without_totals():
+    V, T, K = 8193, 8192, 2
+    mats = delta_matrices(V, T + 1, K, seed=6, density=0.2)
+    views = [m[1:1 + V * T] for m in mats]                      # 4-byte aligned only: cell-wise region
+    assert views[0].data_ptr() % 16 != 0
+    counts = torch.full((V * T,), 2 ** 31 - 2, dtype=torch.int32, device="cuda")
+    run_dense_delta(V, T, views, counts, None)
+    torch.cuda.empty_cache()
+
+
 @pytest.mark.parametrize("big", [511, -512, 512, -513, 1023, 2 ** 30, -2 ** 31])
 def test_binned_path_record_formats(big):
     """Deltas in [-512, 512) travel as 4-byte records through the scratch, any
