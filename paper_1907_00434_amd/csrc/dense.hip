@@ -9,8 +9,11 @@
 // kept through aggregation) and of the server rule (Eq. 2, once per update) is
 // a plain in-register loop; all parallelism is across elements.  Each update is
 // read exactly once with 128-bit loads, model and momentum are read and written
-// exactly once, whatever the number of updates: the kernels are bound by HBM
-// bandwidth and by nothing else.
+// exactly once, whatever the number of updates: the kernels move exactly their
+// algorithmic bytes and are bound by the memory system (hardware counters on 32
+// updates of 61 M elements: vector units busy 16 to 27 % of the time, wavefronts
+// waiting on memory for 50 to 80 % of theirs, every request a full line, no
+// reuse in the L2).
 //
 // Built with -ffp-contract=off: every product and every sum below is rounded
 // on its own, as the definitions in mlfabric.h state.
